@@ -1,0 +1,167 @@
+"""ctypes front end of the CPU fp64 oracle (oracle/sparrow_oracle.c).
+
+TEST INFRASTRUCTURE ONLY: imported by tests/, by the smoke check and by the
+benchmark's cpu_baseline leg.  The HIP library and its Python binding never
+import this package, and this package never imports them.
+
+Every function takes numpy arrays of any float type, widens them to float64
+(exact for fp32 / bf16-representable inputs) and returns float64 / int32
+arrays.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from typing import Optional, Tuple
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "sparrow_oracle.c")
+_LIB = os.path.join(_HERE, "libsparrow_oracle.so")
+
+_dp = ctypes.POINTER(ctypes.c_double)
+_ip = ctypes.POINTER(ctypes.c_int32)
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (-O2, OpenMP).  Returns the library path."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-std=c99", "-Wall", "-Wextra",
+               "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+_lib = None
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        _lib = ctypes.CDLL(build())
+        _lib.oracle_draft_window_attn.restype = ctypes.c_int
+        _lib.oracle_verify_attn.restype = ctypes.c_int
+        _lib.oracle_accept.restype = ctypes.c_int
+        _lib.oracle_logits.restype = None
+        _lib.oracle_argmax.restype = None
+    return _lib
+
+
+def _f64(a) -> np.ndarray:
+    return np.ascontiguousarray(a, dtype=np.float64)
+
+
+def _i32(a) -> np.ndarray:
+    return np.ascontiguousarray(a, dtype=np.int32)
+
+
+def _ptr(a: Optional[np.ndarray], t):
+    return None if a is None else a.ctypes.data_as(t)
+
+
+def default_scale(head_dim: int) -> float:
+    """1/sqrt(d) with d the per-head dimension (reading of "d" in Eq. 2)."""
+    return 1.0 / float(np.sqrt(float(head_dim)))
+
+
+def draft_window_attn(q, k, v, cu_seqlens, text_idx, cu_text, window: int,
+                      scale: Optional[float] = None) -> Tuple[np.ndarray, np.ndarray]:
+    """q [B,Hq,d]; k,v [T,Hkv,d] (position-indexed); returns (out [B,Hq,d], lse [B,Hq])."""
+    q, k, v = _f64(q), _f64(k), _f64(v)
+    B, Hq, d = q.shape
+    T, Hkv, d2 = k.shape
+    assert d2 == d and v.shape == k.shape
+    cu, ti, ct = _i32(cu_seqlens), _i32(text_idx), _i32(cu_text)
+    assert cu.shape == (B + 1,) and ct.shape == (B + 1,)
+    out = np.empty((B, Hq, d), dtype=np.float64)
+    lse = np.empty((B, Hq), dtype=np.float64)
+    sc = default_scale(d) if scale is None else float(scale)
+    rc = _load().oracle_draft_window_attn(
+        _ptr(q, _dp), _ptr(k, _dp), _ptr(v, _dp), _ptr(cu, _ip), _ptr(ti, _ip), _ptr(ct, _ip),
+        ctypes.c_int(B), ctypes.c_int(Hq), ctypes.c_int(Hkv), ctypes.c_int(d),
+        ctypes.c_double(sc), ctypes.c_int(int(window)),
+        ctypes.c_int64(Hkv * d), ctypes.c_int64(d), _ptr(out, _dp), _ptr(lse, _dp))
+    if rc != 0:
+        raise ValueError("oracle_draft_window_attn: invalid arguments")
+    return out, lse
+
+
+def verify_attn(q, k, v, cu_seqlens, parent, n_q: int,
+                scale: Optional[float] = None) -> Tuple[np.ndarray, np.ndarray]:
+    """q [B*n_q,Hq,d]; k,v [sum(L_b+n_q),Hkv,d]; parent int32 [n_q] or None (chain).
+    Returns (out [B*n_q,Hq,d], lse [B*n_q,Hq])."""
+    q, k, v = _f64(q), _f64(k), _f64(v)
+    rows, Hq, d = q.shape
+    T, Hkv, _ = k.shape
+    cu = _i32(cu_seqlens)
+    B = cu.shape[0] - 1
+    assert rows == B * n_q and v.shape == k.shape
+    par = None if parent is None else _i32(parent)
+    out = np.empty((rows, Hq, d), dtype=np.float64)
+    lse = np.empty((rows, Hq), dtype=np.float64)
+    sc = default_scale(d) if scale is None else float(scale)
+    rc = _load().oracle_verify_attn(
+        _ptr(q, _dp), _ptr(k, _dp), _ptr(v, _dp), _ptr(cu, _ip), _ptr(par, _ip),
+        ctypes.c_int(B), ctypes.c_int(int(n_q)), ctypes.c_int(Hq), ctypes.c_int(Hkv),
+        ctypes.c_int(d), ctypes.c_double(sc), ctypes.c_int64(Hkv * d), ctypes.c_int64(d),
+        _ptr(out, _dp), _ptr(lse, _dp))
+    if rc != 0:
+        raise ValueError("oracle_verify_attn: invalid arguments")
+    return out, lse
+
+
+def logits(hidden, lm_head, chunk: int = 8192) -> np.ndarray:
+    """hidden [rows,H] x lm_head [V,H]^T -> [rows,V] float64.  The weight matrix
+    is widened to float64 a block of rows at a time to bound memory."""
+    hidden = _f64(hidden)
+    rows, H = hidden.shape
+    V = lm_head.shape[0]
+    out = np.empty((rows, V), dtype=np.float64)
+    lib = _load()
+    for v0 in range(0, V, chunk):
+        v1 = min(V, v0 + chunk)
+        w = _f64(lm_head[v0:v1])
+        part = np.empty((rows, v1 - v0), dtype=np.float64)
+        lib.oracle_logits(_ptr(hidden, _dp), _ptr(w, _dp), ctypes.c_int(rows), ctypes.c_int(H),
+                          ctypes.c_int64(v1 - v0), _ptr(part, _dp))
+        out[:, v0:v1] = part
+    return out
+
+
+def argmax(lg) -> Tuple[np.ndarray, np.ndarray]:
+    """Per-row greedy token (lowest index on ties) and top-1 minus top-2 margin."""
+    lg = _f64(lg)
+    rows, V = lg.shape
+    ids = np.empty(rows, dtype=np.int32)
+    margin = np.empty(rows, dtype=np.float64)
+    _load().oracle_argmax(_ptr(lg, _dp), ctypes.c_int(rows), ctypes.c_int64(V),
+                          _ptr(ids, _ip), _ptr(margin, _dp))
+    return ids, margin
+
+
+def accept(target_ids, draft_ids, parent, B: int, n_q: int):
+    """Returns (accept_len [B], accept_path [B,n_q], bonus_id [B])."""
+    t, dr = _i32(target_ids), _i32(draft_ids)
+    assert t.shape == (B * (n_q + 1),) and dr.shape == (B * n_q,)
+    par = None if parent is None else _i32(parent)
+    alen = np.empty(B, dtype=np.int32)
+    path = np.empty((B, max(n_q, 0)), dtype=np.int32)
+    bonus = np.empty(B, dtype=np.int32)
+    rc = _load().oracle_accept(_ptr(t, _ip), _ptr(dr, _ip), _ptr(par, _ip), ctypes.c_int(B),
+                               ctypes.c_int(n_q), _ptr(alen, _ip), _ptr(path, _ip),
+                               _ptr(bonus, _ip))
+    if rc != 0:
+        raise ValueError("oracle_accept: invalid parent array")
+    return alen, path, bonus
+
+
+def accept_step(hidden, lm_head, draft_ids, parent, B: int, n_q: int):
+    """lm_head GEMM -> argmax -> greedy acceptance.  Returns a dict with
+    target_ids, margin, accept_len, accept_path, bonus_id."""
+    lg = logits(hidden, lm_head)
+    ids, margin = argmax(lg)
+    alen, path, bonus = accept(ids, draft_ids, parent, B, n_q)
+    return {"target_ids": ids, "margin": margin, "accept_len": alen,
+            "accept_path": path, "bonus_id": bonus}

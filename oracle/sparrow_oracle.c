@@ -1,0 +1,209 @@
+/*
+ * CPU oracle for the Sparrow speculative-decoding hot path.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the plain, slow, fp64 statement of
+ * what the path computes, written from the paper's definitions.  It shares no
+ * code with the HIP library and is never used by it; only the tests, the
+ * smoke check and the benchmark's cpu_baseline leg call it.
+ *
+ * All results here have a plain mathematical definition that the GPU kernels
+ * merely reach by another order of operations (online softmax, split context,
+ * matrix-core tiles), so every function below is that definition written out:
+ * two-pass softmax, no tiling, no splitting, no reordering.  The only
+ * concession to run time is an OpenMP "parallel for" over independent output
+ * rows.
+ *
+ * Pins (tests/test_oracle_*.py): torch's CPU fp64 scaled_dot_product_attention
+ * with an explicit dense mask, scipy's softmax/logsumexp, numpy matmul+argmax,
+ * closed forms (constant V, zero K, one dominant key), invariants (all-text
+ * window == causal decode, n_q = 1 == decode, chain-shaped tree == chain,
+ * per-path decomposition of a tree, row permutation, GQA == replicated MHA),
+ * and brute-force enumeration of small acceptance problems.
+ * Nothing numeric is printed in the paper for these steps, so no golden value
+ * from the paper exists; end-to-end accepted-length tables are out of reach
+ * (trained weights and videos are not available).
+ *
+ * Layout conventions (all row-major, doubles):
+ *   q   [rows, Hq, d]
+ *   K,V token t, kv head c, element x at  t*stride_tok + c*stride_head + x
+ *   out [rows, Hq, d], lse [rows, Hq]
+ * Query head h reads kv head h / (Hq/Hkv)  (contiguous groups).
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+/* Softmax attention of one query vector over an explicit list of key rows:
+ *   s_j = scale * <q, K[tok_j]>,  p = softmax(s),  o = sum_j p_j V[tok_j]
+ * (Eq. 2 with the key set given by `tok`).  Also returns log(sum exp s). */
+static void attend_list(const double *q, const double *K, const double *V,
+                        const int64_t *tok, int n, int d, double scale,
+                        int64_t stride_tok, double *o, double *lse, double *s)
+{
+    double m = -INFINITY;
+    for (int j = 0; j < n; ++j) {
+        const double *kr = K + tok[j] * stride_tok;
+        double acc = 0.0;
+        for (int x = 0; x < d; ++x) acc += q[x] * kr[x];
+        s[j] = scale * acc;
+        if (s[j] > m) m = s[j];
+    }
+    double l = 0.0;
+    for (int j = 0; j < n; ++j) { s[j] = exp(s[j] - m); l += s[j]; }
+    for (int x = 0; x < d; ++x) o[x] = 0.0;
+    for (int j = 0; j < n; ++j) {
+        const double *vr = V + tok[j] * stride_tok;
+        double p = s[j] / l;
+        for (int x = 0; x < d; ++x) o[x] += p * vr[x];
+    }
+    if (lse) *lse = m + log(l);
+}
+
+/* Draft model's text-anchored window attention (VATA, Eq. 2; "discards the
+ * visual KV cache", attention closed within the text domain T).  The window
+ * reading: the `window` most recent text positions; window >= |T| gives Eq. 2
+ * over all of T.  The query's own position is the last text position. */
+int oracle_draft_window_attn(const double *q, const double *K, const double *V,
+                             const int32_t *cu_seqlens, const int32_t *text_idx,
+                             const int32_t *cu_text, int B, int Hq, int Hkv, int d,
+                             double scale, int window,
+                             int64_t stride_tok, int64_t stride_head,
+                             double *out, double *lse)
+{
+    if (Hq % Hkv != 0 || window <= 0) return -1;
+    const int g = Hq / Hkv;
+    for (int b = 0; b < B; ++b)
+        if (cu_text[b + 1] - cu_text[b] <= 0) return -1; /* softmax over nothing */
+    #pragma omp parallel for collapse(2) schedule(dynamic, 1)
+    for (int b = 0; b < B; ++b) {
+        for (int h = 0; h < Hq; ++h) {
+            const int n_text = cu_text[b + 1] - cu_text[b];
+            const int n = n_text < window ? n_text : window;
+            const int32_t *idx = text_idx + cu_text[b] + (n_text - n);
+            int64_t *tok = (int64_t *)malloc(sizeof(int64_t) * (size_t)n);
+            double *s = (double *)malloc(sizeof(double) * (size_t)n);
+            for (int j = 0; j < n; ++j) tok[j] = (int64_t)cu_seqlens[b] + idx[j];
+            const int c = h / g;
+            attend_list(q + ((int64_t)b * Hq + h) * d, K + c * stride_head, V + c * stride_head,
+                        tok, n, d, scale, stride_tok,
+                        out + ((int64_t)b * Hq + h) * d,
+                        lse ? lse + (int64_t)b * Hq + h : NULL, s);
+            free(tok); free(s);
+        }
+    }
+    return 0;
+}
+
+/* Target's verification attention: n_q draft rows per sequence, each seeing
+ * the whole context of its sequence plus, among the draft rows, itself and
+ * its ancestors in the draft tree (parent[i] in [-1, i); NULL = chain, i.e.
+ * row i sees draft rows 0..i).  Sequence b owns rows cu_seqlens[b] ..
+ * cu_seqlens[b+1]-1 of K/V: L_b context rows followed by its n_q draft rows. */
+int oracle_verify_attn(const double *q, const double *K, const double *V,
+                       const int32_t *cu_seqlens, const int32_t *parent,
+                       int B, int n_q, int Hq, int Hkv, int d, double scale,
+                       int64_t stride_tok, int64_t stride_head,
+                       double *out, double *lse)
+{
+    if (Hq % Hkv != 0) return -1;
+    const int g = Hq / Hkv;
+    for (int i = 0; parent && i < n_q; ++i)
+        if (parent[i] < -1 || parent[i] >= i) return -1;
+    for (int b = 0; b < B; ++b)
+        if (cu_seqlens[b + 1] - cu_seqlens[b] < n_q) return -1;
+    #pragma omp parallel for collapse(2) schedule(dynamic, 1)
+    for (int b = 0; b < B; ++b) {
+        for (int i = 0; i < n_q; ++i) {
+            const int L = cu_seqlens[b + 1] - cu_seqlens[b] - n_q;
+            int64_t *tok = (int64_t *)malloc(sizeof(int64_t) * (size_t)(L + n_q));
+            double *s = (double *)malloc(sizeof(double) * (size_t)(L + n_q));
+            int n = 0;
+            for (int t = 0; t < L; ++t) tok[n++] = (int64_t)cu_seqlens[b] + t;
+            if (parent) {
+                /* ancestors-or-self, then put them in ascending order */
+                int first = n;
+                for (int a = i; a >= 0; a = parent[a]) tok[n++] = (int64_t)cu_seqlens[b] + L + a;
+                for (int lo = first, hi = n - 1; lo < hi; ++lo, --hi) {
+                    int64_t tmp = tok[lo]; tok[lo] = tok[hi]; tok[hi] = tmp;
+                }
+            } else {
+                for (int a = 0; a <= i; ++a) tok[n++] = (int64_t)cu_seqlens[b] + L + a;
+            }
+            for (int h = 0; h < Hq; ++h) {
+                const int c = h / g;
+                const int64_t row = (int64_t)b * n_q + i;
+                attend_list(q + (row * Hq + h) * d, K + c * stride_head, V + c * stride_head,
+                            tok, n, d, scale, stride_tok,
+                            out + (row * Hq + h) * d,
+                            lse ? lse + row * Hq + h : NULL, s);
+            }
+            free(tok); free(s);
+        }
+    }
+    return 0;
+}
+
+/* lm_head: logits[r, v] = sum_x hidden[r, x] * W[v, x]   (no bias). */
+void oracle_logits(const double *hidden, const double *W, int rows, int H, int64_t vocab,
+                   double *logits)
+{
+    #pragma omp parallel for schedule(static)
+    for (int64_t v = 0; v < vocab; ++v) {
+        const double *w = W + v * H;
+        for (int r = 0; r < rows; ++r) {
+            const double *hr = hidden + (int64_t)r * H;
+            double acc = 0.0;
+            for (int x = 0; x < H; ++x) acc += hr[x] * w[x];
+            logits[(int64_t)r * vocab + v] = acc;
+        }
+    }
+}
+
+/* Greedy (temperature 0) target token per row: the smallest index attaining
+ * the row maximum.  margin[r] = best - second best (0 on an exact tie). */
+void oracle_argmax(const double *logits, int rows, int64_t vocab, int32_t *ids, double *margin)
+{
+    for (int r = 0; r < rows; ++r) {
+        const double *lr = logits + (int64_t)r * vocab;
+        int64_t best = 0;
+        for (int64_t v = 1; v < vocab; ++v) if (lr[v] > lr[best]) best = v;
+        double second = -INFINITY;
+        for (int64_t v = 0; v < vocab; ++v) if (v != best && lr[v] > second) second = lr[v];
+        ids[r] = (int32_t)best;
+        if (margin) margin[r] = vocab > 1 ? lr[best] - second : INFINITY;
+    }
+}
+
+/* Greedy acceptance (lossless at temperature 0): starting from the last
+ * accepted token (row 0 of each sequence's n_q+1 rows), repeatedly move to the
+ * child whose drafted token equals the target's greedy token at the current
+ * row; the lowest-numbered such child wins.  Row 1+i belongs to draft node i.
+ * Outputs: accept_len [B], accept_path [B, n_q] (node indices root-first, -1
+ * padded), bonus_id [B] = target token at the last accepted row. */
+int oracle_accept(const int32_t *target_ids, const int32_t *draft_ids, const int32_t *parent,
+                  int B, int n_q, int32_t *accept_len, int32_t *accept_path, int32_t *bonus_id)
+{
+    for (int i = 0; parent && i < n_q; ++i)
+        if (parent[i] < -1 || parent[i] >= i) return -1;
+    for (int b = 0; b < B; ++b) {
+        const int32_t *t = target_ids + (int64_t)b * (n_q + 1);
+        const int32_t *dr = draft_ids + (int64_t)b * n_q;
+        int32_t *path = accept_path + (int64_t)b * n_q;
+        for (int i = 0; i < n_q; ++i) path[i] = -1;
+        int cur = -1, len = 0;
+        for (;;) {
+            int next = -1;
+            for (int j = 0; j < n_q && next < 0; ++j) {
+                const int pj = parent ? parent[j] : j - 1;
+                if (pj == cur && dr[j] == t[cur + 1]) next = j;
+            }
+            if (next < 0) break;
+            path[len++] = next;
+            cur = next;
+        }
+        accept_len[b] = len;
+        bonus_id[b] = t[cur + 1];
+    }
+    return 0;
+}
