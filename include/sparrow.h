@@ -1,0 +1,163 @@
+/*
+ * sparrow.h — C ABI of the MI355X (gfx950) hot path of one Sparrow
+ * speculative-decoding step for video LLMs:
+ *
+ *   sparrow_draft_window_attn   draft model's text-anchored window attention
+ *   sparrow_verify_attn         target model's verification attention
+ *   sparrow_accept              lm_head GEMM -> per-row argmax -> greedy acceptance
+ *
+ * C99, no C++ or HIP types.  "dev" pointers are device (HBM) addresses, "host"
+ * pointers are ordinary host memory.
+ *
+ * Common rules
+ *  - Ownership: the caller owns every buffer, the workspace included.  The
+ *    library never allocates or frees device memory and keeps no pointer
+ *    after a call returns.
+ *  - Asynchrony: a call validates its scalar and host arguments, enqueues its
+ *    kernels on `hip_stream` (a hipStream_t passed as void*, NULL = the default
+ *    stream) and returns without synchronising.  Host arrays are fully read
+ *    before the call returns.  Device buffers must stay valid until the
+ *    stream has passed the enqueued work.  Calls are graph-capturable.
+ *  - Errors: every entry point returns a sparrow_status (0 = ok, negative =
+ *    error); on error nothing has been enqueued and sparrow_last_error()
+ *    describes the reason.  Contents of device arrays (text_idx ascending and
+ *    in range, parent[i] in [-1, i)) are preconditions that cannot be checked
+ *    without a device read; violating them gives undefined results but never
+ *    an out-of-bounds access as long as indices stay inside the sequence.
+ *  - Types: SPARROW_F32 tensors hold IEEE float, SPARROW_BF16 tensors hold
+ *    bfloat16; all arithmetic accumulates in fp32.  Device pointers must be
+ *    16-byte aligned, head_dim is innermost and contiguous.
+ *  - Query head h reads KV head h / (n_q_heads / n_kv_heads).
+ */
+#ifndef SPARROW_H
+#define SPARROW_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  SPARROW_OK = 0,
+  SPARROW_ERR_INVALID_ARG = -1,  /* NULL pointer, bad size, misaligned pointer, bad host array */
+  SPARROW_ERR_UNSUPPORTED = -2,  /* dtype / head_dim / size outside what the kernels cover */
+  SPARROW_ERR_WORKSPACE = -3,    /* workspace NULL or smaller than the *_workspace() query */
+  SPARROW_ERR_DEVICE = -4        /* the HIP runtime refused a launch */
+} sparrow_status;
+
+typedef enum { SPARROW_F32 = 0, SPARROW_BF16 = 1 } sparrow_dtype;
+
+/* Limits (SPARROW_ERR_UNSUPPORTED beyond them). */
+#define SPARROW_MAX_BATCH 64   /* sequences per call */
+#define SPARROW_MAX_NQ 64      /* draft rows (chain length or tree nodes) per sequence */
+
+/* Shared by both attention calls. */
+typedef struct {
+  int32_t dtype;        /* sparrow_dtype of q, k, v and out */
+  int32_t n_q_heads;    /* Hq */
+  int32_t n_kv_heads;   /* Hkv, divides Hq */
+  int32_t head_dim;     /* d: 64 or 128 */
+  float scale;          /* softmax scale; 0 selects 1/sqrt(head_dim), the per-head reading of
+                           the "d" of Eq. 2 */
+  int64_t kv_stride_token; /* elements between consecutive tokens of k (and of v) */
+  int64_t kv_stride_head;  /* elements between consecutive KV heads of one token */
+} sparrow_attn_desc;
+
+/*
+ * Draft model's visually-aware text-anchored window attention (Section
+ * "Visually-Aware Text-Anchored Window Attention via Hidden State Reuse",
+ * Eq. 2): for every sequence b and query head h,
+ *     out[b,h,:] = softmax(scale * q[b,h,:] . K_T^T) V_T
+ * where T is the set of the min(window, n_text_b) most recent text positions
+ * of sequence b.  Keys and values at visual positions are never addressed: the
+ * kernel walks `text_idx`, the precomputed position-type index.
+ *
+ *  q          dev [B, Hq, d]      the one draft query of each sequence
+ *  k, v       dev                 draft-layer K/V indexed by absolute position; token t of
+ *                                 sequence b, head c starts at element
+ *                                 (cu_seqlens[b] + t)*kv_stride_token + c*kv_stride_head
+ *  cu_seqlens host int32 [B+1]    token offset of every sequence in k/v (ascending)
+ *  text_idx   dev  int32          ascending sequence-local text positions, sequences packed
+ *  cu_text    host int32 [B+1]    offsets into text_idx; every sequence needs >= 1 text position
+ *                                 (the query's own position is the last one)
+ *  window     > 0                 clamped to the sequence's number of text positions
+ *  out        dev [B, Hq, d]      same dtype as q
+ *  lse        dev float [B, Hq]   natural-log sum-exp of the scaled scores, or NULL
+ *  workspace  unused by this call (size query returns 0); may be NULL
+ */
+size_t sparrow_draft_window_attn_workspace(const sparrow_attn_desc *desc, int32_t B,
+                                           int32_t window);
+int sparrow_draft_window_attn(const sparrow_attn_desc *desc, const void *q, const void *k,
+                              const void *v, const int32_t *cu_seqlens, const int32_t *text_idx,
+                              const int32_t *cu_text, int32_t B, int32_t window, void *out,
+                              float *lse, void *workspace, size_t workspace_bytes,
+                              void *hip_stream);
+
+/*
+ * Target model's verification attention (the "parallel verification by the
+ * target model" of the draft-then-verify loop, Introduction; dynamic draft
+ * trees, Experiment section): n_q draft rows per sequence are scored in one
+ * pass against the sequence's whole KV cache.  Row i of sequence b attends to
+ * all L_b context tokens and, among the n_q draft tokens, to itself and its
+ * ancestors in the draft tree.
+ *
+ *  q          dev [B*n_q, Hq, d]
+ *  k, v       dev               per sequence: L_b context rows followed by its n_q draft rows
+ *  cu_seqlens host int32 [B+1]  sequence b owns rows cu_seqlens[b] .. cu_seqlens[b+1]-1
+ *                               (= L_b + n_q rows, L_b >= 0)
+ *  parent     dev int32 [n_q]   tree shared by all sequences: parent[i] in [-1, i), -1 = child of
+ *                               the last accepted token; NULL = chain (parent[i] = i-1)
+ *  out        dev [B*n_q, Hq, d]
+ *  lse        dev float [B*n_q, Hq] or NULL
+ *  workspace  dev, at least sparrow_verify_attn_workspace() bytes, 256-byte aligned; holds the
+ *             split-context partial results (running max, sum, unnormalised output)
+ *  total_tokens = cu_seqlens[B]
+ *  B = 0 or n_q = 0: SPARROW_OK and nothing is enqueued.
+ */
+size_t sparrow_verify_attn_workspace(const sparrow_attn_desc *desc, int32_t B, int32_t n_q,
+                                     int64_t total_tokens);
+int sparrow_verify_attn(const sparrow_attn_desc *desc, const void *q, const void *k,
+                        const void *v, const int32_t *cu_seqlens, const int32_t *parent,
+                        int32_t B, int32_t n_q, void *out, float *lse, void *workspace,
+                        size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Greedy (temperature 0, lossless) acceptance: logits = hidden_rows . lm_head^T,
+ * target token of every row = lowest index attaining the row maximum, then the
+ * longest accepted path: starting at the last accepted token (row 0), move to
+ * the lowest-numbered child whose drafted token equals the target token of the
+ * current row, until no child matches.  Tokens generated by the step =
+ * accept_len + 1 (the bonus token), the paper's average accepted length.
+ *
+ *  hidden_rows dev [B*(n_q+1), hidden]  row 0 of a sequence = last accepted token, row 1+i =
+ *                                       draft node i; final norm already applied
+ *  lm_head     dev [vocab, hidden]      row-major, no bias
+ *  draft_ids   dev int32 [B*n_q]
+ *  parent      dev int32 [n_q] or NULL (chain)
+ *  target_ids  dev int32 out [B*(n_q+1)]
+ *  accept_len  dev int32 out [B]        in [0, tree depth]
+ *  accept_path dev int32 out [B*n_q]    accepted node indices root-first, -1 padded
+ *  bonus_id    dev int32 out [B]        target token at the last accepted row
+ *  workspace   dev, at least sparrow_accept_workspace() bytes (per-tile argmax candidates)
+ *  Limits: B*(n_q+1) <= 64 rows.  n_q = 0 is allowed (plain greedy decode of row 0).
+ */
+size_t sparrow_accept_workspace(int32_t dtype, int32_t B, int32_t n_q, int32_t hidden,
+                                int32_t vocab);
+int sparrow_accept(int32_t dtype, const void *hidden_rows, const void *lm_head,
+                   const int32_t *draft_ids, const int32_t *parent, int32_t B, int32_t n_q,
+                   int32_t hidden, int32_t vocab, int32_t *target_ids, int32_t *accept_len,
+                   int32_t *accept_path, int32_t *bonus_id, void *workspace,
+                   size_t workspace_bytes, void *hip_stream);
+
+/* Thread-local description of the last error on this thread; "" if none. */
+const char *sparrow_last_error(void);
+
+/* Library version, "major.minor". */
+const char *sparrow_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SPARROW_H */

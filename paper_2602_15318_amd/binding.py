@@ -1,0 +1,206 @@
+"""ctypes binding of libsparrow.so: argument marshalling only.
+
+Function names and argument order follow include/sparrow.h.  Tensors are torch tensors on the
+GPU; the host arrays (cu_seqlens, cu_text) are numpy arrays / sequences of ints.  There is no
+fallback: if the HIP library has not been built, importing this module raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Sequence
+
+import numpy as np
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libsparrow.so")
+
+SPARROW_F32 = 0
+SPARROW_BF16 = 1
+
+
+class SparrowError(RuntimeError):
+    def __init__(self, code: int, message: str):
+        super().__init__(f"sparrow status {code}: {message}")
+        self.code = code
+
+
+class AttnDesc(ctypes.Structure):
+    _fields_ = [("dtype", ctypes.c_int32), ("n_q_heads", ctypes.c_int32),
+                ("n_kv_heads", ctypes.c_int32), ("head_dim", ctypes.c_int32),
+                ("scale", ctypes.c_float), ("kv_stride_token", ctypes.c_int64),
+                ("kv_stride_head", ctypes.c_int64)]
+
+
+def _load() -> ctypes.CDLL:
+    if not os.path.exists(_LIB_PATH):
+        raise ImportError(
+            f"{_LIB_PATH} is missing: build it with `python -m paper_2602_15318_amd.build` "
+            "(or __graft_entry__.build()); there is no fallback path")
+    L = ctypes.CDLL(_LIB_PATH)
+    vp, i32p, fp = ctypes.c_void_p, ctypes.POINTER(ctypes.c_int32), ctypes.c_void_p
+    dp = ctypes.POINTER(AttnDesc)
+    L.sparrow_last_error.restype = ctypes.c_char_p
+    L.sparrow_version.restype = ctypes.c_char_p
+    L.sparrow_draft_window_attn_workspace.restype = ctypes.c_size_t
+    L.sparrow_draft_window_attn_workspace.argtypes = [dp, ctypes.c_int32, ctypes.c_int32]
+    L.sparrow_draft_window_attn.restype = ctypes.c_int
+    L.sparrow_draft_window_attn.argtypes = [dp, vp, vp, vp, i32p, vp, i32p, ctypes.c_int32,
+                                            ctypes.c_int32, vp, fp, vp, ctypes.c_size_t, vp]
+    L.sparrow_verify_attn_workspace.restype = ctypes.c_size_t
+    L.sparrow_verify_attn_workspace.argtypes = [dp, ctypes.c_int32, ctypes.c_int32, ctypes.c_int64]
+    L.sparrow_verify_attn.restype = ctypes.c_int
+    L.sparrow_verify_attn.argtypes = [dp, vp, vp, vp, i32p, vp, ctypes.c_int32, ctypes.c_int32,
+                                      vp, fp, vp, ctypes.c_size_t, vp]
+    L.sparrow_accept_workspace.restype = ctypes.c_size_t
+    L.sparrow_accept_workspace.argtypes = [ctypes.c_int32] * 5
+    L.sparrow_accept.restype = ctypes.c_int
+    L.sparrow_accept.argtypes = [ctypes.c_int32, vp, vp, vp, vp, ctypes.c_int32, ctypes.c_int32,
+                                 ctypes.c_int32, ctypes.c_int32, vp, vp, vp, vp, vp,
+                                 ctypes.c_size_t, vp]
+    return L
+
+
+lib = _load()
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def version() -> str:
+    return lib.sparrow_version().decode()
+
+
+def last_error() -> str:
+    return lib.sparrow_last_error().decode()
+
+
+def _check(rc: int) -> None:
+    if rc != 0:
+        raise SparrowError(rc, last_error())
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return SPARROW_F32
+    if t.dtype == torch.bfloat16:
+        return SPARROW_BF16
+    raise TypeError(f"unsupported tensor dtype {t.dtype}")
+
+
+def _host_i32(a) -> np.ndarray:
+    return np.ascontiguousarray(np.asarray(a), dtype=np.int32)
+
+
+def _i32p(a: np.ndarray):
+    return a.ctypes.data_as(ctypes.POINTER(ctypes.c_int32))
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream_ptr(stream) -> ctypes.c_void_p:
+    s = torch.cuda.current_stream() if stream is None else stream
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+def _desc(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, scale: float) -> AttnDesc:
+    if k.dim() != 3 or k.stride(2) != 1 or v.stride() != k.stride() or v.shape != k.shape:
+        raise ValueError("k and v must be [T, Hkv, d] with identical strides and a contiguous d")
+    if not q.is_contiguous():
+        raise ValueError("q must be contiguous [rows, Hq, d]")
+    return AttnDesc(_dtype_code(q), q.shape[1], k.shape[1], q.shape[2], float(scale),
+                    k.stride(0), k.stride(1))
+
+
+def _workspace(nbytes: int, device, workspace: Optional[torch.Tensor]) -> Optional[torch.Tensor]:
+    if workspace is not None:
+        return workspace
+    if nbytes == 0:
+        return None
+    return torch.empty(nbytes, dtype=torch.uint8, device=device)
+
+
+def draft_window_attn(q, k, v, cu_seqlens, text_idx, cu_text, window: int, scale: float = 0.0,
+                      out=None, lse=None, want_lse: bool = True, stream=None):
+    """sparrow_draft_window_attn.  q [B,Hq,d]; k,v [T,Hkv,d]; text_idx int32 device tensor.
+    Returns (out, lse)."""
+    B = q.shape[0]
+    d = _desc(q, k, v, scale)
+    cu, ct = _host_i32(cu_seqlens), _host_i32(cu_text)
+    if cu.shape != (B + 1,) or ct.shape != (B + 1,):
+        raise ValueError("cu_seqlens and cu_text must have B+1 entries")
+    if text_idx.dtype != torch.int32 or not text_idx.is_contiguous():
+        raise ValueError("text_idx must be a contiguous int32 tensor")
+    out = torch.empty_like(q) if out is None else out
+    if lse is None and want_lse:
+        lse = torch.empty(q.shape[:2], dtype=torch.float32, device=q.device)
+    _check(lib.sparrow_draft_window_attn(ctypes.byref(d), _ptr(q), _ptr(k), _ptr(v), _i32p(cu),
+                                         _ptr(text_idx), _i32p(ct), B, int(window), _ptr(out),
+                                         _ptr(lse), None, 0, _stream_ptr(stream)))
+    return out, lse
+
+
+def verify_attn_workspace_bytes(q, k, v, B: int, n_q: int, total_tokens: int,
+                                scale: float = 0.0) -> int:
+    d = _desc(q, k, v, scale)
+    return int(lib.sparrow_verify_attn_workspace(ctypes.byref(d), B, n_q, int(total_tokens)))
+
+
+def verify_attn(q, k, v, cu_seqlens, parent, n_q: int, scale: float = 0.0, out=None, lse=None,
+                want_lse: bool = True, workspace=None, stream=None):
+    """sparrow_verify_attn.  q [B*n_q,Hq,d]; k,v [sum(L_b+n_q),Hkv,d]; parent int32 device
+    tensor [n_q] or None (chain).  Returns (out, lse)."""
+    cu = _host_i32(cu_seqlens)
+    B = cu.shape[0] - 1
+    d = _desc(q, k, v, scale)
+    if parent is not None and (parent.dtype != torch.int32 or parent.numel() != n_q):
+        raise ValueError("parent must be an int32 tensor with n_q entries")
+    out = torch.empty_like(q) if out is None else out
+    if lse is None and want_lse:
+        lse = torch.empty(q.shape[:2], dtype=torch.float32, device=q.device)
+    need = int(lib.sparrow_verify_attn_workspace(ctypes.byref(d), B, n_q, int(cu[-1]))) if B > 0 else 0
+    ws = _workspace(need, q.device, workspace)
+    _check(lib.sparrow_verify_attn(ctypes.byref(d), _ptr(q), _ptr(k), _ptr(v), _i32p(cu),
+                                   _ptr(parent), B, int(n_q), _ptr(out), _ptr(lse), _ptr(ws),
+                                   0 if ws is None else ws.numel() * ws.element_size(),
+                                   _stream_ptr(stream)))
+    return out, lse
+
+
+def accept_workspace_bytes(dtype_code: int, B: int, n_q: int, hidden: int, vocab: int) -> int:
+    return int(lib.sparrow_accept_workspace(dtype_code, B, n_q, hidden, vocab))
+
+
+def accept(hidden_rows, lm_head, draft_ids, parent, B: int, n_q: int, workspace=None,
+           outputs=None, stream=None):
+    """sparrow_accept.  hidden_rows [B*(n_q+1), H]; lm_head [V, H]; draft_ids int32 [B*n_q].
+    Returns a dict of int32 device tensors: target_ids, accept_len, accept_path, bonus_id."""
+    if not hidden_rows.is_contiguous() or not lm_head.is_contiguous():
+        raise ValueError("hidden_rows and lm_head must be contiguous")
+    if hidden_rows.dtype != lm_head.dtype:
+        raise ValueError("hidden_rows and lm_head must share a dtype")
+    H, V = hidden_rows.shape[1], lm_head.shape[0]
+    if hidden_rows.shape[0] != B * (n_q + 1) or lm_head.shape[1] != H:
+        raise ValueError("shape mismatch between hidden_rows, lm_head, B and n_q")
+    dev = hidden_rows.device
+    code = _dtype_code(hidden_rows)
+    if outputs is None:
+        outputs = {"target_ids": torch.empty(B * (n_q + 1), dtype=torch.int32, device=dev),
+                   "accept_len": torch.empty(B, dtype=torch.int32, device=dev),
+                   "accept_path": torch.empty(B, max(n_q, 1), dtype=torch.int32, device=dev)[:, :n_q],
+                   "bonus_id": torch.empty(B, dtype=torch.int32, device=dev)}
+    ws = _workspace(accept_workspace_bytes(code, B, n_q, H, V), dev, workspace)
+    path = outputs["accept_path"]
+    if n_q > 0 and not path.is_contiguous():
+        raise ValueError("accept_path must be contiguous")
+    _check(lib.sparrow_accept(code, _ptr(hidden_rows), _ptr(lm_head), _ptr(draft_ids),
+                              _ptr(parent), B, n_q, H, V, _ptr(outputs["target_ids"]),
+                              _ptr(outputs["accept_len"]), _ptr(path) if n_q > 0 else None,
+                              _ptr(outputs["bonus_id"]), _ptr(ws),
+                              0 if ws is None else ws.numel() * ws.element_size(),
+                              _stream_ptr(stream)))
+    return outputs

@@ -1,0 +1,31 @@
+// Internal interface of the acceptance kernels (lm_head GEMM + argmax + greedy walk).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/sparrow.h"
+
+namespace sparrow {
+
+constexpr int kAcceptMaxRows = 64;
+
+struct AcceptArgs {
+  const void *hidden;        // [M, H]
+  const void *lm_head;       // [V, H]
+  const int32_t *draft_ids;  // [B*n_q]
+  const int32_t *parent;     // [n_q] or nullptr
+  int32_t B, n_q, M, H, V;   // M = B*(n_q+1)
+  int32_t n_cand;            // argmax candidates per row produced by the GEMM pass
+  float *cand_val;           // [M, n_cand]
+  int32_t *cand_idx;         // [M, n_cand]
+  int32_t *target_ids, *accept_len, *accept_path, *bonus_id;
+};
+
+// Number of per-row argmax candidates the GEMM pass writes (one per wavefront / tile owner).
+int accept_num_candidates(int dtype, int M, int H, int V);
+bool lm_head_mfma_supported(int dtype, int M, int H, int V);
+hipError_t launch_lm_head_generic(int dtype, const AcceptArgs &a, hipStream_t st);
+hipError_t launch_lm_head_mfma(const AcceptArgs &a, hipStream_t st);
+hipError_t launch_accept_finalize(const AcceptArgs &a, hipStream_t st);
+
+}  // namespace sparrow

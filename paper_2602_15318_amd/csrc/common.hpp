@@ -1,0 +1,94 @@
+// Device-side helpers shared by the Sparrow HIP kernels (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace sparrow {
+
+typedef unsigned short bf16_t;  // raw bfloat16 bits
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
+typedef __attribute__((ext_vector_type(2))) unsigned int u32x2;
+
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+// Finite stand-in for "no score seen yet": exp2(kNegBig - x) underflows to 0 for any real x and
+// kNegBig - kNegBig = 0 never produces a NaN.
+constexpr float kNegBig = -1.0e30f;
+
+__device__ __forceinline__ float bf16_to_f32(bf16_t b) {
+  return __uint_as_float(((unsigned int)b) << 16);
+}
+// Two packed bf16 (low half = element 0) -> floats.
+__device__ __forceinline__ float bf16lo_to_f32(unsigned int w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16hi_to_f32(unsigned int w) {
+  return __uint_as_float(w & 0xffff0000u);
+}
+// Round to nearest even; inputs are finite or +-inf (NaN is passed through as a quiet NaN).
+__device__ __forceinline__ bf16_t f32_to_bf16(float f) {
+  unsigned int u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((u >> 16) | 0x40u);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (bf16_t)(u >> 16);
+}
+__device__ __forceinline__ unsigned int pack_bf16x2(float lo, float hi) {
+  return (unsigned int)f32_to_bf16(lo) | ((unsigned int)f32_to_bf16(hi) << 16);
+}
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+__device__ __forceinline__ float fast_log2(float x) { return __builtin_amdgcn_logf(x); }
+
+// Element type traits for kernels templated on the storage type.
+template <typename T> struct Elem;
+template <> struct Elem<float> {
+  static constexpr int kPer16B = 4;
+  static __device__ __forceinline__ void unpack(const u32x4 &w, float *f) {
+    f[0] = __uint_as_float(w.x); f[1] = __uint_as_float(w.y);
+    f[2] = __uint_as_float(w.z); f[3] = __uint_as_float(w.w);
+  }
+  static __device__ __forceinline__ float load(const float *p) { return *p; }
+  static __device__ __forceinline__ void store(float *p, float v) { *p = v; }
+};
+template <> struct Elem<bf16_t> {
+  static constexpr int kPer16B = 8;
+  static __device__ __forceinline__ void unpack(const u32x4 &w, float *f) {
+    f[0] = bf16lo_to_f32(w.x); f[1] = bf16hi_to_f32(w.x);
+    f[2] = bf16lo_to_f32(w.y); f[3] = bf16hi_to_f32(w.y);
+    f[4] = bf16lo_to_f32(w.z); f[5] = bf16hi_to_f32(w.z);
+    f[6] = bf16lo_to_f32(w.w); f[7] = bf16hi_to_f32(w.w);
+  }
+  static __device__ __forceinline__ float load(const bf16_t *p) { return bf16_to_f32(*p); }
+  static __device__ __forceinline__ void store(bf16_t *p, float v) { *p = f32_to_bf16(v); }
+};
+
+// Butterfly reductions over a 64-lane wavefront (all lanes get the result).
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  return v;
+}
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+
+// Ancestor-or-self bit set of draft row i: bit j set <=> row i may attend draft row j.
+// parent == nullptr means a chain.  Requires parent[a] < a (then the walk ends) and i < 64.
+__device__ __forceinline__ unsigned long long ancestor_mask(const int32_t *parent, int i) {
+  if (parent == nullptr) return (2ull << i) - 1ull;
+  unsigned long long m = 0;
+  int a = i;
+  // At most i+1 steps: a strictly decreases for a valid tree; the counter bounds the walk for
+  // an invalid one.
+  for (int steps = 0; a >= 0 && steps <= i; ++steps) {
+    m |= 1ull << a;
+    int p = parent[a];
+    a = (p < a) ? p : -1;
+  }
+  return m;
+}
+
+}  // namespace sparrow

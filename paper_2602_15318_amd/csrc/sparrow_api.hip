@@ -1,0 +1,260 @@
+// Host side of the C ABI declared in include/sparrow.h: argument validation, split planning,
+// kernel selection and launches.  No device allocation, no synchronisation, no device reads.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+
+#include "../../include/sparrow.h"
+#include "accept.hpp"
+#include "draft_window_attn.hpp"
+#include "verify_attn.hpp"
+
+namespace sparrow {
+int generic_num_candidates(int V);
+
+namespace {
+thread_local char g_err[512] = "";
+
+int fail(int code, const char *fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+constexpr int kNumCU = 256;   // MI355X
+
+int check_desc(const sparrow_attn_desc *d) {
+  if (!d) return fail(SPARROW_ERR_INVALID_ARG, "desc is NULL");
+  if (d->dtype != SPARROW_F32 && d->dtype != SPARROW_BF16)
+    return fail(SPARROW_ERR_UNSUPPORTED, "dtype %d is neither SPARROW_F32 nor SPARROW_BF16", d->dtype);
+  if (d->n_q_heads <= 0 || d->n_kv_heads <= 0 || d->n_q_heads % d->n_kv_heads != 0)
+    return fail(SPARROW_ERR_INVALID_ARG, "n_q_heads %d must be a positive multiple of n_kv_heads %d",
+                d->n_q_heads, d->n_kv_heads);
+  if (d->head_dim != 64 && d->head_dim != 128)
+    return fail(SPARROW_ERR_UNSUPPORTED, "head_dim %d (supported: 64, 128)", d->head_dim);
+  const int per = d->dtype == SPARROW_BF16 ? 8 : 4;
+  if (d->kv_stride_head < d->head_dim || d->kv_stride_head % per != 0 ||
+      d->kv_stride_token < d->kv_stride_head * d->n_kv_heads || d->kv_stride_token % per != 0)
+    return fail(SPARROW_ERR_INVALID_ARG,
+                "kv strides (token %lld, head %lld) must be multiples of 16 bytes with "
+                "stride_head >= head_dim and stride_token >= n_kv_heads*stride_head",
+                (long long)d->kv_stride_token, (long long)d->kv_stride_head);
+  if (!(d->scale >= 0.f) || std::isinf(d->scale))
+    return fail(SPARROW_ERR_INVALID_ARG, "scale must be finite and >= 0 (0 = 1/sqrt(head_dim))");
+  return SPARROW_OK;
+}
+
+float scale_log2_of(const sparrow_attn_desc *d) {
+  const float s = d->scale > 0.f ? d->scale : 1.0f / std::sqrt((float)d->head_dim);
+  return s * 1.4426950408889634f;
+}
+
+// Tokens per context split.  Aim at about one workgroup per compute unit: the split partials are
+// pure overhead traffic, so no more splits than it takes to occupy the chip.
+int plan_chunk(const sparrow_attn_desc *d, int32_t n_q, int64_t total_tokens, bool mfma) {
+  const int R = n_q * (d->n_q_heads / d->n_kv_heads);
+  const int rows_per_wg = mfma ? 64 : 16;
+  const int rbs = (R + rows_per_wg - 1) / rows_per_wg;
+  int slots = kNumCU / (d->n_kv_heads * rbs);
+  if (slots < 1) slots = 1;
+  int64_t chunk = (total_tokens + slots - 1) / slots;
+  chunk = (int64_t)round_up((size_t)chunk, 32);
+  if (chunk < 64) chunk = 64;
+  return (int)chunk;
+}
+
+bool use_mfma_verify(const sparrow_attn_desc *d) {
+  return verify_partial_mfma_supported(d->dtype, d->head_dim);
+}
+
+size_t verify_ws_bytes(const sparrow_attn_desc *d, int64_t max_slots, int32_t n_q) {
+  const size_t rows = (size_t)max_slots * n_q * d->n_q_heads;
+  return round_up(rows * d->head_dim * sizeof(float), 256) + round_up(rows * 2 * sizeof(float), 256);
+}
+}  // namespace
+}  // namespace sparrow
+
+using namespace sparrow;
+
+extern "C" {
+
+const char *sparrow_last_error(void) { return g_err; }
+const char *sparrow_version(void) { return "0.1"; }
+
+// ------------------------------------------------------------------ draft window attention
+size_t sparrow_draft_window_attn_workspace(const sparrow_attn_desc *, int32_t, int32_t) { return 0; }
+
+int sparrow_draft_window_attn(const sparrow_attn_desc *desc, const void *q, const void *k,
+                              const void *v, const int32_t *cu_seqlens, const int32_t *text_idx,
+                              const int32_t *cu_text, int32_t B, int32_t window, void *out,
+                              float *lse, void *workspace, size_t workspace_bytes,
+                              void *hip_stream) {
+  (void)workspace; (void)workspace_bytes;
+  g_err[0] = 0;
+  if (int rc = check_desc(desc)) return rc;
+  if (B < 0) return fail(SPARROW_ERR_INVALID_ARG, "B = %d is negative", B);
+  if (B == 0) return SPARROW_OK;
+  if (B > SPARROW_MAX_BATCH) return fail(SPARROW_ERR_UNSUPPORTED, "B = %d exceeds %d", B, SPARROW_MAX_BATCH);
+  if (window <= 0) return fail(SPARROW_ERR_INVALID_ARG, "window = %d must be positive", window);
+  if (!q || !k || !v || !cu_seqlens || !text_idx || !cu_text || !out)
+    return fail(SPARROW_ERR_INVALID_ARG, "NULL pointer among q/k/v/cu_seqlens/text_idx/cu_text/out");
+  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out))
+    return fail(SPARROW_ERR_INVALID_ARG, "q, k, v and out must be 16-byte aligned");
+  DraftTable tab;
+  memset(&tab, 0, sizeof(tab));
+  if (cu_seqlens[0] < 0 || cu_text[0] < 0)
+    return fail(SPARROW_ERR_INVALID_ARG, "cu_seqlens[0] and cu_text[0] must be >= 0");
+  for (int b = 0; b <= B; ++b) { tab.cu_len[b] = cu_seqlens[b]; tab.cu_text[b] = cu_text[b]; }
+  for (int b = 0; b < B; ++b) {
+    const int len = cu_seqlens[b + 1] - cu_seqlens[b], nt = cu_text[b + 1] - cu_text[b];
+    if (len <= 0) return fail(SPARROW_ERR_INVALID_ARG, "sequence %d has %d tokens", b, len);
+    if (nt <= 0)
+      return fail(SPARROW_ERR_INVALID_ARG,
+                  "sequence %d has no text position: softmax over an empty set is undefined", b);
+    if (nt > len)
+      return fail(SPARROW_ERR_INVALID_ARG, "sequence %d: %d text positions in %d tokens", b, nt, len);
+  }
+  DraftArgs a;
+  a.q = q; a.k = k; a.v = v; a.text_idx = text_idx;
+  a.B = B; a.Hq = desc->n_q_heads; a.Hkv = desc->n_kv_heads; a.d = desc->head_dim;
+  a.window = window;
+  a.scale_log2 = scale_log2_of(desc);
+  a.stride_tok = desc->kv_stride_token; a.stride_head = desc->kv_stride_head;
+  a.out = out; a.lse = lse;
+  hipError_t e = launch_draft_window_attn(desc->dtype, a, tab, (hipStream_t)hip_stream);
+  if (e != hipSuccess) return fail(SPARROW_ERR_DEVICE, "draft_window_attn launch: %s", hipGetErrorString(e));
+  return SPARROW_OK;
+}
+
+// ------------------------------------------------------------------ verification attention
+size_t sparrow_verify_attn_workspace(const sparrow_attn_desc *desc, int32_t B, int32_t n_q,
+                                     int64_t total_tokens) {
+  if (check_desc(desc) != SPARROW_OK || B <= 0 || n_q <= 0 || total_tokens <= 0) return 0;
+  const int chunk = plan_chunk(desc, n_q, total_tokens, use_mfma_verify(desc));
+  const int64_t max_slots = (total_tokens + chunk - 1) / chunk + B;
+  return verify_ws_bytes(desc, max_slots, n_q);
+}
+
+int sparrow_verify_attn(const sparrow_attn_desc *desc, const void *q, const void *k,
+                        const void *v, const int32_t *cu_seqlens, const int32_t *parent,
+                        int32_t B, int32_t n_q, void *out, float *lse, void *workspace,
+                        size_t workspace_bytes, void *hip_stream) {
+  g_err[0] = 0;
+  if (int rc = check_desc(desc)) return rc;
+  if (B < 0 || n_q < 0) return fail(SPARROW_ERR_INVALID_ARG, "B = %d, n_q = %d: negative", B, n_q);
+  if (B == 0 || n_q == 0) return SPARROW_OK;
+  if (B > SPARROW_MAX_BATCH) return fail(SPARROW_ERR_UNSUPPORTED, "B = %d exceeds %d", B, SPARROW_MAX_BATCH);
+  if (n_q > SPARROW_MAX_NQ) return fail(SPARROW_ERR_UNSUPPORTED, "n_q = %d exceeds %d", n_q, SPARROW_MAX_NQ);
+  if (!q || !k || !v || !cu_seqlens || !out)
+    return fail(SPARROW_ERR_INVALID_ARG, "NULL pointer among q/k/v/cu_seqlens/out");
+  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out))
+    return fail(SPARROW_ERR_INVALID_ARG, "q, k, v and out must be 16-byte aligned");
+  if (cu_seqlens[0] < 0) return fail(SPARROW_ERR_INVALID_ARG, "cu_seqlens[0] must be >= 0");
+  for (int b = 0; b < B; ++b)
+    if (cu_seqlens[b + 1] - cu_seqlens[b] < n_q)
+      return fail(SPARROW_ERR_INVALID_ARG, "sequence %d has %d rows, fewer than its n_q = %d draft rows",
+                  b, cu_seqlens[b + 1] - cu_seqlens[b], n_q);
+  const int64_t total = cu_seqlens[B];   // the figure the workspace query is given
+  const bool mfma = use_mfma_verify(desc);
+  const int chunk = plan_chunk(desc, n_q, total, mfma);
+  SeqTable tab;
+  memset(&tab, 0, sizeof(tab));
+  for (int b = 0; b <= B; ++b) tab.cu_len[b] = cu_seqlens[b];
+  for (int b = 0; b < B; ++b) {
+    const int len = cu_seqlens[b + 1] - cu_seqlens[b];
+    tab.cu_split[b + 1] = tab.cu_split[b] + (len + chunk - 1) / chunk;
+  }
+  const int n_slots = tab.cu_split[B];
+  const size_t need = verify_ws_bytes(desc, n_slots, n_q);
+  if (!workspace || workspace_bytes < need)
+    return fail(SPARROW_ERR_WORKSPACE, "workspace of %zu bytes needed, %zu given%s", need,
+                workspace_bytes, workspace ? "" : " (NULL)");
+  if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0)
+    return fail(SPARROW_ERR_INVALID_ARG, "workspace must be 256-byte aligned");
+  VerifyArgs a;
+  a.q = q; a.k = k; a.v = v; a.parent = parent;
+  a.B = B; a.n_q = n_q; a.Hq = desc->n_q_heads; a.Hkv = desc->n_kv_heads; a.d = desc->head_dim;
+  a.chunk = chunk; a.n_slots = n_slots;
+  a.scale_log2 = scale_log2_of(desc);
+  a.stride_tok = desc->kv_stride_token; a.stride_head = desc->kv_stride_head;
+  const size_t rows = (size_t)n_slots * n_q * desc->n_q_heads;
+  a.part_o = (float *)workspace;
+  a.part_ml = (float *)((char *)workspace + round_up(rows * desc->head_dim * sizeof(float), 256));
+  a.out = out; a.lse = lse;
+  hipStream_t st = (hipStream_t)hip_stream;
+  hipError_t e = mfma ? launch_verify_partial_mfma(a, tab, st)
+                      : launch_verify_partial_generic(desc->dtype, a, tab, st);
+  if (e != hipSuccess) return fail(SPARROW_ERR_DEVICE, "verify partial launch: %s", hipGetErrorString(e));
+  e = launch_verify_combine(desc->dtype, a, tab, st);
+  if (e != hipSuccess) return fail(SPARROW_ERR_DEVICE, "verify combine launch: %s", hipGetErrorString(e));
+  return SPARROW_OK;
+}
+
+// ------------------------------------------------------------------ acceptance
+static int accept_candidates(int32_t dtype, int M, int H, int V) {
+  if (lm_head_mfma_supported(dtype, M, H, V)) return accept_num_candidates(dtype, M, H, V);
+  return generic_num_candidates(V);
+}
+
+size_t sparrow_accept_workspace(int32_t dtype, int32_t B, int32_t n_q, int32_t hidden,
+                                int32_t vocab) {
+  if (B <= 0 || n_q < 0 || hidden <= 0 || vocab <= 0) return 0;
+  const int M = B * (n_q + 1);
+  const size_t n = (size_t)M * accept_candidates(dtype, M, hidden, vocab);
+  return round_up(n * sizeof(float), 256) + round_up(n * sizeof(int32_t), 256);
+}
+
+int sparrow_accept(int32_t dtype, const void *hidden_rows, const void *lm_head,
+                   const int32_t *draft_ids, const int32_t *parent, int32_t B, int32_t n_q,
+                   int32_t hidden, int32_t vocab, int32_t *target_ids, int32_t *accept_len,
+                   int32_t *accept_path, int32_t *bonus_id, void *workspace,
+                   size_t workspace_bytes, void *hip_stream) {
+  g_err[0] = 0;
+  if (dtype != SPARROW_F32 && dtype != SPARROW_BF16)
+    return fail(SPARROW_ERR_UNSUPPORTED, "dtype %d is neither SPARROW_F32 nor SPARROW_BF16", dtype);
+  if (B < 0 || n_q < 0) return fail(SPARROW_ERR_INVALID_ARG, "B = %d, n_q = %d: negative", B, n_q);
+  if (B == 0) return SPARROW_OK;
+  if (n_q > SPARROW_MAX_NQ) return fail(SPARROW_ERR_UNSUPPORTED, "n_q = %d exceeds %d", n_q, SPARROW_MAX_NQ);
+  if ((int64_t)B * (n_q + 1) > kAcceptMaxRows)
+    return fail(SPARROW_ERR_UNSUPPORTED, "B*(n_q+1) = %lld rows exceeds %d", (long long)B * (n_q + 1), kAcceptMaxRows);
+  if (hidden <= 0 || vocab <= 0) return fail(SPARROW_ERR_INVALID_ARG, "hidden = %d, vocab = %d", hidden, vocab);
+  const int per = dtype == SPARROW_BF16 ? 8 : 4;
+  if (hidden % per != 0)
+    return fail(SPARROW_ERR_UNSUPPORTED, "hidden = %d must be a multiple of %d (16-byte rows)", hidden, per);
+  if (!hidden_rows || !lm_head || !target_ids || !accept_len || !bonus_id ||
+      (n_q > 0 && (!draft_ids || !accept_path)))
+    return fail(SPARROW_ERR_INVALID_ARG, "NULL pointer among hidden_rows/lm_head/draft_ids/outputs");
+  if (!aligned16(hidden_rows) || !aligned16(lm_head))
+    return fail(SPARROW_ERR_INVALID_ARG, "hidden_rows and lm_head must be 16-byte aligned");
+  const int M = B * (n_q + 1);
+  const bool mfma = lm_head_mfma_supported(dtype, M, hidden, vocab);
+  const int n_cand = accept_candidates(dtype, M, hidden, vocab);
+  const size_t need = sparrow_accept_workspace(dtype, B, n_q, hidden, vocab);
+  if (!workspace || workspace_bytes < need)
+    return fail(SPARROW_ERR_WORKSPACE, "workspace of %zu bytes needed, %zu given%s", need,
+                workspace_bytes, workspace ? "" : " (NULL)");
+  if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0)
+    return fail(SPARROW_ERR_INVALID_ARG, "workspace must be 256-byte aligned");
+  AcceptArgs a;
+  a.hidden = hidden_rows; a.lm_head = lm_head; a.draft_ids = draft_ids; a.parent = parent;
+  a.B = B; a.n_q = n_q; a.M = M; a.H = hidden; a.V = vocab; a.n_cand = n_cand;
+  a.cand_val = (float *)workspace;
+  a.cand_idx = (int32_t *)((char *)workspace + round_up((size_t)M * n_cand * sizeof(float), 256));
+  a.target_ids = target_ids; a.accept_len = accept_len; a.accept_path = accept_path;
+  a.bonus_id = bonus_id;
+  hipStream_t st = (hipStream_t)hip_stream;
+  hipError_t e = mfma ? launch_lm_head_mfma(a, st) : launch_lm_head_generic(dtype, a, st);
+  if (e != hipSuccess) return fail(SPARROW_ERR_DEVICE, "lm_head launch: %s", hipGetErrorString(e));
+  e = launch_accept_finalize(a, st);
+  if (e != hipSuccess) return fail(SPARROW_ERR_DEVICE, "accept finalize launch: %s", hipGetErrorString(e));
+  return SPARROW_OK;
+}
+
+}  // extern "C"

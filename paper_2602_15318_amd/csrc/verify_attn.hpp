@@ -1,0 +1,49 @@
+// Internal interface of the verification-attention kernels.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/sparrow.h"
+
+namespace sparrow {
+
+// Per-call schedule, passed to the kernels by value (no device-side schedule buffer, so a call is
+// a pure function of its arguments and can be captured in a graph).  The context of every
+// sequence is cut into splits of `chunk` tokens; split slots are numbered across sequences.
+struct SeqTable {
+  int32_t cu_len[SPARROW_MAX_BATCH + 1];    // token offsets (L_b + n_q rows per sequence)
+  int32_t cu_split[SPARROW_MAX_BATCH + 1];  // split-slot offsets
+};
+
+struct VerifyArgs {
+  const void *q, *k, *v;
+  const int32_t *parent;  // device, or nullptr for a chain
+  int32_t B, n_q, Hq, Hkv, d;
+  int32_t chunk;          // tokens per split
+  int32_t n_slots;        // cu_split[B]
+  float scale_log2;       // softmax scale * log2(e)
+  int64_t stride_tok, stride_head;
+  float *part_o;          // [n_slots, n_q, Hq, d]   unnormalised partial outputs
+  float *part_ml;         // [n_slots, n_q, Hq, 2]   running max (log2 domain), partial sum
+  void *out;              // [B*n_q, Hq, d]
+  float *lse;             // [B*n_q, Hq] or nullptr
+};
+
+// Which sequence owns split slot `slot` (linear scan; B <= SPARROW_MAX_BATCH).
+__device__ __forceinline__ int seq_of_slot(const SeqTable &tab, int B, int slot) {
+  int b = 0;
+  while (b + 1 < B && tab.cu_split[b + 1] <= slot) ++b;
+  return b;
+}
+
+// Partial pass, plain-ALU version: any supported dtype / head_dim.
+hipError_t launch_verify_partial_generic(int dtype, const VerifyArgs &a, const SeqTable &tab,
+                                         hipStream_t st);
+// Partial pass, matrix-core version: bf16, head_dim 128.
+bool verify_partial_mfma_supported(int dtype, int head_dim);
+hipError_t launch_verify_partial_mfma(const VerifyArgs &a, const SeqTable &tab, hipStream_t st);
+// Second pass: merge the per-split partials of every (row, head).
+hipError_t launch_verify_combine(int dtype, const VerifyArgs &a, const SeqTable &tab,
+                                 hipStream_t st);
+
+}  // namespace sparrow

@@ -1,0 +1,178 @@
+"""GPU parity of the two attention entry points against the CPU fp64 oracle, element by element
+on the same seeded inputs, through the C-ABI."""
+import numpy as np
+import pytest
+
+import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def sp():
+    import torch
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    import paper_2602_15318_amd as sp_
+    return sp_
+
+
+from gpu_util import check_attn, run_draft, run_verify  # noqa: E402
+
+LSE_TOL = {"f32": 2e-5, "bf16": 2e-2}
+
+
+def _verify_and_check(sp, oracle, c, what):
+    out, lse = run_verify(sp, c)
+    ref, ref_lse = oracle.verify_attn(c.q, c.k, c.v, c.cu_seqlens, c.parent, c.n_q)
+    err = check_attn(out, ref, c.cfg.dtype, what)
+    assert np.abs(lse - ref_lse).max() <= LSE_TOL[c.cfg.dtype], f"{what}: lse"
+    return err
+
+
+def _draft_and_check(sp, oracle, c, what):
+    out, lse = run_draft(sp, c)
+    ref, ref_lse = oracle.draft_window_attn(c.q, c.k, c.v, c.cu_seqlens, c.text_idx, c.cu_text,
+                                            c.window)
+    err = check_attn(out, ref, c.cfg.dtype, what)
+    assert np.abs(lse - ref_lse).max() <= LSE_TOL[c.cfg.dtype], f"{what}: lse"
+    return err
+
+
+# ------------------------------------------------------------------ the five configurations
+@pytest.mark.parametrize("peaked", [False, True])
+def test_c1_fp32(sp, oracle, peaked):
+    _verify_and_check(sp, oracle, wl.verify_case(wl.C1, 0, peaked=peaked), "C1 verify")
+    _draft_and_check(sp, oracle, wl.draft_case(wl.C1, 0, peaked=peaked), "C1 draft")
+
+
+@pytest.mark.parametrize("peaked", [False, True])
+def test_c2_bf16_8k_chain5(sp, oracle, peaked):
+    _verify_and_check(sp, oracle, wl.verify_case(wl.C2, 0, peaked=peaked), "C2 verify")
+    _draft_and_check(sp, oracle, wl.draft_case(wl.C2, 0, peaked=peaked), "C2 draft")
+
+
+@pytest.mark.parametrize("peaked", [False, True])
+def test_c3_bf16_26k_tree60(sp, oracle, peaked):
+    c = wl.verify_case(wl.C3, 0, peaked=peaked)
+    assert c.parent is not None and len(c.parent) == 60
+    _verify_and_check(sp, oracle, c, "C3 verify")
+    _draft_and_check(sp, oracle, wl.draft_case(wl.C3, 0, peaked=peaked), "C3 draft")
+
+
+@pytest.mark.parametrize("peaked", [False, True])
+def test_c4_bf16_ragged_batch8(sp, oracle, peaked):
+    _verify_and_check(sp, oracle, wl.verify_case(wl.C4, 0, peaked=peaked), "C4 verify")
+    _draft_and_check(sp, oracle, wl.draft_case(wl.C4, 0, peaked=peaked), "C4 draft")
+
+
+@pytest.mark.parametrize("layer", [0, 27])
+def test_c5_bf16_26k_chain8_layer(sp, oracle, layer):
+    """One layer of the benchmarked workload at its full size and launch configuration."""
+    _verify_and_check(sp, oracle, wl.verify_case(wl.C5, 0, layer=layer, peaked=(layer == 27)),
+                      f"C5 verify layer {layer}")
+    if layer == 0:
+        _draft_and_check(sp, oracle, wl.draft_case(wl.C5, 0), "C5 draft")
+
+
+# ------------------------------------------------------------------ shapes, tails, degenerate cases
+def _cfg(dtype, Hq, Hkv, d, n_q=4, window=16):
+    return wl.Config("T", dtype, Hq, Hkv, d, 1, None, window, n_q, False, 64, 128)
+
+
+SHAPES = [("f32", 4, 1, 64), ("f32", 8, 2, 128), ("bf16", 8, 2, 64), ("bf16", 28, 4, 128),
+          ("bf16", 16, 16, 128), ("bf16", 32, 4, 128)]
+
+
+@pytest.mark.parametrize("dtype,Hq,Hkv,d", SHAPES)
+@pytest.mark.parametrize("L", [0, 1, 31, 33, 257, 1500])
+def test_verify_context_lengths(sp, oracle, dtype, Hq, Hkv, d, L):
+    """Context lengths around tile boundaries, including an empty context (only the draft rows)."""
+    cfg = _cfg(dtype, Hq, Hkv, d)
+    lay = (((wl.TEXT, L),),) if L > 0 else (((wl.TEXT, 0),),)
+    for n_q in (1, 3, 8):
+        c = wl.verify_case(cfg, seed=L + n_q, layouts=lay, n_q=n_q, parent=None)
+        _verify_and_check(sp, oracle, c, f"verify {dtype} {Hq}/{Hkv}/{d} L={L} n_q={n_q}")
+
+
+@pytest.mark.parametrize("dtype,Hq,Hkv,d", [("f32", 4, 1, 64), ("bf16", 28, 4, 128)])
+def test_verify_trees(sp, oracle, dtype, Hq, Hkv, d):
+    cfg = _cfg(dtype, Hq, Hkv, d)
+    lay = (((wl.TEXT, 700),), ((wl.TEXT, 90),))
+    trees = [wl.chain_parent(7), np.full(5, -1, dtype=np.int32),
+             wl.pruned_tree(1, 25, (4, 2, 2, 1, 1)), wl.pruned_tree(2, 30, (8, 2, 1, 1)),
+             wl.pruned_tree(3, 48, (10, 2, 2, 1, 1)), wl.pruned_tree(4, 64, (4, 4, 2, 2, 1, 1))]
+    for ti, parent in enumerate(trees):
+        c = wl.verify_case(cfg, seed=50 + ti, layouts=lay, n_q=len(parent), parent=parent)
+        _verify_and_check(sp, oracle, c, f"tree {ti} ({len(parent)} nodes) {dtype}")
+    # a chain given as a tree gives bit-identical output to parent = NULL
+    c = wl.verify_case(cfg, seed=60, layouts=lay, n_q=6, parent=None)
+    a, _ = run_verify(sp, c)
+    c.parent = wl.chain_parent(6)
+    b, _ = run_verify(sp, c)
+    np.testing.assert_array_equal(a, b)
+
+
+@pytest.mark.parametrize("dtype,Hq,Hkv,d", SHAPES)
+def test_draft_windows_and_layouts(sp, oracle, dtype, Hq, Hkv, d):
+    cfg = _cfg(dtype, Hq, Hkv, d)
+    lays = (((wl.TEXT, 5), (wl.VISUAL, 400), (wl.TEXT, 3), (wl.VISUAL, 170), (wl.TEXT, 90)),
+            ((wl.VISUAL, 300), (wl.TEXT, 1)),
+            ((wl.TEXT, 700),))
+    for window in (1, 2, 63, 64, 65, 98, 512, 4096):
+        c = wl.draft_case(cfg, seed=window, layouts=lays, window=window)
+        _draft_and_check(sp, oracle, c, f"draft {dtype} {Hq}/{Hkv}/{d} W={window}")
+
+
+def test_draft_ignores_poisoned_visual_kv(sp, oracle):
+    """NaN in every visual K/V slot: the kernel never addresses them."""
+    c = wl.draft_case(wl.C2, 1)
+    ref, _ = oracle.draft_window_attn(c.q, c.k, c.v, c.cu_seqlens, c.text_idx, c.cu_text, c.window)
+    vis = np.flatnonzero(c.types[0] == wl.VISUAL)
+    c.k[vis] = np.nan
+    c.v[vis] = np.nan
+    out, _ = run_draft(sp, c)
+    check_attn(out, ref, "bf16", "poisoned visual KV")
+
+
+def test_strided_kv_and_explicit_scale(sp, oracle):
+    """K/V given as slices of a wider buffer (non-default strides) and a caller-chosen scale."""
+    import torch
+    from gpu_util import dev, host
+    cfg = _cfg("bf16", 28, 4, 128)
+    c = wl.verify_case(cfg, seed=5, layouts=(((wl.TEXT, 900),),), n_q=5, parent=None)
+    T = c.k.shape[0]
+    wide_k = torch.zeros(T, 6, 160, dtype=torch.bfloat16, device="cuda")
+    wide_v = torch.zeros_like(wide_k)
+    wide_k[:, 1:5, 16:144] = dev(c.k, "bf16")
+    wide_v[:, 1:5, 16:144] = dev(c.v, "bf16")
+    out, _ = sp.verify_attn(dev(c.q, "bf16"), wide_k[:, 1:5, 16:144], wide_v[:, 1:5, 16:144],
+                            c.cu_seqlens, None, 5, scale=0.05)
+    torch.cuda.synchronize()
+    ref, _ = oracle.verify_attn(c.q, c.k, c.v, c.cu_seqlens, None, 5, scale=0.05)
+    check_attn(host(out), ref, "bf16", "strided kv")
+
+
+def test_argument_errors(sp):
+    import torch
+    from gpu_util import dev
+    c = wl.verify_case(_cfg("bf16", 28, 4, 128), seed=6, layouts=(((wl.TEXT, 100),),), n_q=3,
+                       parent=None)
+    q, k, v = dev(c.q, "bf16"), dev(c.k, "bf16"), dev(c.v, "bf16")
+    with pytest.raises(sp.SparrowError) as e:   # workspace too small
+        sp.verify_attn(q, k, v, c.cu_seqlens, None, 3,
+                       workspace=torch.empty(256, dtype=torch.uint8, device="cuda"))
+    assert e.value.code == -3
+    with pytest.raises(sp.SparrowError) as e:   # a sequence shorter than n_q
+        sp.verify_attn(q, k, v, np.array([0, 2], dtype=np.int32), None, 3)
+    assert e.value.code == -1
+    d = wl.draft_case(_cfg("bf16", 28, 4, 128), seed=7, layouts=(((wl.TEXT, 100),),))
+    with pytest.raises(sp.SparrowError) as e:   # empty text domain
+        sp.draft_window_attn(dev(d.q, "bf16"), dev(d.k, "bf16"), dev(d.v, "bf16"), d.cu_seqlens,
+                             dev(d.text_idx), np.array([0, 0], dtype=np.int32), 8)
+    assert e.value.code == -1 and "text" in str(e.value)
+    with pytest.raises(sp.SparrowError):        # window <= 0
+        sp.draft_window_attn(dev(d.q, "bf16"), dev(d.k, "bf16"), dev(d.v, "bf16"), d.cu_seqlens,
+                             dev(d.text_idx), d.cu_text, 0)
+    # B = 0 / n_q = 0 are no-ops
+    out, _ = sp.verify_attn(q[:0], k, v, np.array([0, 103], dtype=np.int32), None, 0)
+    assert out.numel() == 0
