@@ -1,0 +1,237 @@
+#!/usr/bin/env python3
+"""Benchmark of the Sparrow hot path on one MI355X.
+
+A step is one pass of the whole hot path over workload C5: 28 layers of verification attention
+(28 query / 4 KV heads, head_dim 128, chain of 8 draft rows against a 26,112-token context of
+which 25,088 are visual), one draft window attention (window 512 over the text positions) and one
+greedy acceptance (lm_head 152,064 x 3584 on 9 rows, argmax, longest accepted prefix).  All in
+bf16 with synthetic seeded inputs already resident in HBM.  The step is captured once in a HIP
+graph and replayed, so the timed region holds GPU work only.
+
+Prints ONE JSON line (see README for the fields).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+from concurrent.futures import ThreadPoolExecutor
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0   # MI355X HBM3E, published
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--profile-only", action="store_true",
+                    help="run warmup + steps only (for rocprofv3), skip the per-op timing legs")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print(f"bench.py: this build runs on one GPU only (no collectives, no sharding); "
+              f"--gpus {args.gpus} is not supported", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    import paper_2602_15318_amd as sp
+    import workloads as wl
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    cfg = wl.C5
+    bf16 = torch.bfloat16
+
+    def dev(x, dt=None):
+        t = torch.from_numpy(np.ascontiguousarray(x)).to("cuda")
+        return t if dt is None else t.to(dt)
+
+    # ---------------------------------------------------------------- inputs (seeded, synthetic)
+    t_gen = time.time()
+    with ThreadPoolExecutor(max_workers=8) as pool:
+        cases = list(pool.map(lambda l: wl.verify_case(cfg, args.seed, layer=l), range(cfg.n_layers)))
+    cu = cases[0].cu_seqlens
+    layers = [(dev(c.q, bf16), dev(c.k, bf16), dev(c.v, bf16)) for c in cases]
+    layer0 = cases[0]
+    del cases
+    dcase = wl.draft_case(cfg, args.seed)
+    dq, dk, dv = dev(dcase.q, bf16), dev(dcase.k, bf16), dev(dcase.v, bf16)
+    dtext = dev(dcase.text_idx)
+    acase = wl.accept_case(cfg, args.seed)
+    hidden, lm_head = dev(acase.hidden, bf16), dev(acase.lm_head, bf16)
+    draft_ids = dev(acase.draft_ids)
+    t_gen = time.time() - t_gen
+
+    n_q, Hq, Hkv, d = cfg.n_q, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim
+    T = int(cu[-1])                                    # 26,112 context + 8 draft rows
+    # ---------------------------------------------------------------- caller-owned buffers
+    ws_v = torch.empty(sp.verify_attn_workspace_bytes(*layers[0], 1, n_q, T), dtype=torch.uint8,
+                       device="cuda")
+    ws_a = torch.empty(sp.accept_workspace_bytes(1, 1, n_q, cfg.hidden, cfg.vocab),
+                       dtype=torch.uint8, device="cuda")
+    v_out = [torch.empty_like(q) for q, _, _ in layers]
+    d_out = torch.empty_like(dq)
+    a_out = {"target_ids": torch.empty(n_q + 1, dtype=torch.int32, device="cuda"),
+             "accept_len": torch.empty(1, dtype=torch.int32, device="cuda"),
+             "accept_path": torch.empty(1, n_q, dtype=torch.int32, device="cuda"),
+             "bonus_id": torch.empty(1, dtype=torch.int32, device="cuda")}
+
+    def verify_layer(l):
+        q, k, v = layers[l]
+        sp.verify_attn(q, k, v, cu, None, n_q, out=v_out[l], want_lse=False, workspace=ws_v)
+
+    def draft():
+        sp.draft_window_attn(dq, dk, dv, dcase.cu_seqlens, dtext, dcase.cu_text, cfg.window,
+                             out=d_out, want_lse=False)
+
+    def accept():
+        sp.accept(hidden, lm_head, draft_ids, None, 1, n_q, workspace=ws_a, outputs=a_out)
+
+    def step():
+        draft()                      # draft phase (one window-attention call of it)
+        for l in range(cfg.n_layers):
+            verify_layer(l)          # verify phase
+        accept()
+
+    def capture(fn):
+        g = torch.cuda.CUDAGraph()
+        s = torch.cuda.Stream()
+        s.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(s):
+            fn()                     # eager once on the side stream (first-call set-up)
+        torch.cuda.current_stream().wait_stream(s)
+        torch.cuda.synchronize()
+        with torch.cuda.graph(g):
+            fn()
+        return g
+
+    def time_graph(g, reps, warm=3):
+        for _ in range(warm):
+            g.replay()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            g.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e3 / reps      # us per replay
+
+    # ---------------------------------------------------------------- the timed region
+    g_step = capture(step)
+    for _ in range(args.warmup):
+        g_step.replay()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        g_step.replay()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    us_step = (t1 - t0) * 1e6 / args.steps
+    if args.profile_only:
+        print(json.dumps({"profile_only": True, "us_per_step": us_step}))
+        return 0
+
+    # algorithmic bytes (bf16): K and V once, Q in and O out; lm_head weights once
+    esz = 2
+    bytes_verify_layer = 2 * T * Hkv * d * esz + 2 * n_q * Hq * d * esz
+    n_win = min(cfg.window, int(dcase.cu_text[1]))
+    bytes_draft = 2 * n_win * Hkv * d * esz + 2 * Hq * d * esz
+    bytes_accept = cfg.vocab * cfg.hidden * esz + (n_q + 1) * cfg.hidden * esz
+    bytes_step = cfg.n_layers * bytes_verify_layer + bytes_draft + bytes_accept
+
+    # ---------------------------------------------------------------- per-op legs (HIP events)
+    def verify_all():
+        for l in range(cfg.n_layers):
+            verify_layer(l)
+    us_verify_step = time_graph(capture(verify_all), max(5, args.steps // 2))
+    us_draft = time_graph(capture(draft), 200)
+    us_accept = time_graph(capture(accept), 20)
+
+    # dominant kernel: the verify-attention launch(es) of one layer.  Events bracket every call;
+    # a queued-up device (a long fill first) keeps CPU launch latency out of the intervals.
+    reps = 4
+    n_calls = reps * cfg.n_layers
+    evs = [torch.cuda.Event(enable_timing=True) for _ in range(n_calls + 1)]
+    big = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
+    for _ in range(32):
+        big.fill_(1)
+    for i in range(n_calls):
+        evs[i].record()
+        verify_layer(i % cfg.n_layers)
+    evs[n_calls].record()
+    torch.cuda.synchronize()
+    per_call = sorted(evs[i].elapsed_time(evs[i + 1]) * 1e3 for i in range(n_calls))
+    us_layer_events = float(np.mean(per_call))
+    del big
+    us_layer = us_verify_step / cfg.n_layers       # back-to-back average inside the graph
+    gbps_layer = bytes_verify_layer / us_layer * 1e-3
+
+    result = {
+        "metric": "verify-attn HBM GB/s at 25k ctx over the full verify step "
+                  "(28-layer verify attention + draft window attention + lm_head/argmax/accept)",
+        "value": round(bytes_step / us_step * 1e-3, 1),
+        "unit": "GB/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(us_step * 1e-3, 5),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "C5: 28 layers x verify attn (28/4 heads, d128, chain k=8, ctx "
+                               "26,112 = 512 text + 25,088 visual + 512 text) + draft window attn "
+                               "(W=512) + lm_head 152,064x3584 on 9 rows + argmax + greedy accept",
+                   "batch": 1, "seed": args.seed, "launch": "HIP graph replay"},
+        "bytes_per_step": bytes_step,
+        "us_per_step": round(us_step, 2),
+        "verify_attn_us_per_step": round(us_verify_step, 2),
+        "verify_attn_us_per_layer": round(us_layer, 3),
+        "verify_attn_gbps": round(gbps_layer, 1),
+        "verify_attn_pct_hbm_peak": round(100 * gbps_layer / HBM_PEAK_GBPS, 2),
+        "verify_attn_us_per_layer_eventpairs": round(us_layer_events, 3),
+        "draft_attn_us": round(us_draft, 3),
+        "accept_us": round(us_accept, 2),
+        "accept_gbps": round(bytes_accept / us_accept * 1e-3, 1),
+        "roofline": {"bound": "hbm", "kernel": "verify attention, one layer (all launches of one "
+                                               "sparrow_verify_attn call)",
+                     "achieved": round(gbps_layer, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": round(gbps_layer / HBM_PEAK_GBPS, 4), "traffic": None,
+                     "algorithmic_bytes_per_launch": bytes_verify_layer},
+        "context": "paper: 2.82x average decoding speedup, LLaVA-OneVision-7B on NVIDIA L20, 25K "
+                   "visual tokens, T=0 (end-to-end, other hardware; not comparable)",
+        "input_gen_s": round(t_gen, 1),
+    }
+
+    # ---------------------------------------------------------------- CPU oracle beside it
+    if not args.no_cpu_baseline:
+        import oracle
+        cores = len(os.sched_getaffinity(0))
+        vs = 16384                                   # vocabulary rows of the lm_head sample
+        tc = time.perf_counter()
+        oracle.verify_attn(layer0.q, layer0.k, layer0.v, layer0.cu_seqlens, None, n_q)
+        oracle.draft_window_attn(dcase.q, dcase.k, dcase.v, dcase.cu_seqlens, dcase.text_idx,
+                                 dcase.cu_text, cfg.window)
+        lg = oracle.logits(acase.hidden, acase.lm_head[:vs])
+        oracle.argmax(lg)
+        tc = time.perf_counter() - tc
+        sample_bytes = bytes_verify_layer + bytes_draft + vs * cfg.hidden * esz
+        result["cpu_baseline"] = {
+            "value": round(sample_bytes / tc * 1e-9, 4), "unit": "GB/s", "cores": cores,
+            "kind": "oracle", "seconds": round(tc, 2),
+            "sample": f"1 of 28 verify layers + the draft window call + lm_head on the first {vs} "
+                      f"of 152,064 vocabulary rows (fp64 oracle, OpenMP; includes widening the "
+                      f"inputs to fp64)"}
+    print(json.dumps(result))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

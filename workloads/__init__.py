@@ -22,6 +22,7 @@ both lossless.
 """
 from __future__ import annotations
 
+from concurrent.futures import ThreadPoolExecutor
 from dataclasses import dataclass, field
 from typing import List, Optional, Sequence, Tuple
 
@@ -318,10 +319,19 @@ def lm_head_weights(cfg: Config, seed: int = 0, vocab: Optional[int] = None) -> 
     V = cfg.vocab if vocab is None else vocab
     out = np.empty((V, cfg.hidden), dtype=np.float32)
     blk = 8192
-    for i, r0 in enumerate(range(0, V, blk)):
+
+    def fill(i: int) -> None:
+        r0 = i * blk
         r1 = min(V, r0 + blk)
         rng = _rng(seed, 501, i)
         out[r0:r1] = _normal(rng, (blk, cfg.hidden), cfg.dtype, 0.02)[: r1 - r0]
+
+    n_blk = (V + blk - 1) // blk
+    if n_blk == 1:
+        fill(0)
+    else:   # independent streams per block: drawing them concurrently changes nothing
+        with ThreadPoolExecutor(max_workers=min(8, n_blk)) as pool:
+            list(pool.map(fill, range(n_blk)))
     return out
 
 
