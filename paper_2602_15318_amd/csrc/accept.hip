@@ -80,27 +80,30 @@ __global__ void __launch_bounds__(256) lm_head_generic_kernel(AcceptArgs a) {
   }
 }
 
-// One workgroup of 1024 threads: 16 lanes per row reduce that row's candidates, then one thread
-// per sequence walks the chain / tree.
+// One workgroup of 16 wavefronts: wavefront w reduces the candidates of rows w, w+16, ... (64 lanes
+// stride over the row's candidates, then a butterfly), then one thread per sequence walks the
+// chain / tree.
 __global__ void __launch_bounds__(1024) accept_finalize_kernel(AcceptArgs a) {
   __shared__ int32_t tgt[kAcceptMaxRows];
   const int tid = threadIdx.x;
-  const int r = tid / 16, sl = tid % 16;
-  if (r < a.M) {
+  const int w = tid >> 6, lane = tid & 63;
+  for (int r = w; r < a.M; r += 16) {
     float bv = -INFINITY;
     int bi = 0x7fffffff;
-    for (int c = sl; c < a.n_cand; c += 16) {
-      const float v = a.cand_val[(int64_t)r * a.n_cand + c];
-      const int i = a.cand_idx[(int64_t)r * a.n_cand + c];
+    const float *cv = a.cand_val + (int64_t)r * a.n_cand;
+    const int32_t *ci = a.cand_idx + (int64_t)r * a.n_cand;
+    for (int c = lane; c < a.n_cand; c += 64) {
+      const float v = cv[c];
+      const int i = ci[c];
       if (v > bv || (v == bv && i < bi)) { bv = v; bi = i; }
     }
 #pragma unroll
-    for (int o = 8; o >= 1; o >>= 1) {
+    for (int o = 32; o >= 1; o >>= 1) {
       const float ov = __shfl_xor(bv, o, 64);
       const int oi = __shfl_xor(bi, o, 64);
       if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
     }
-    if (sl == 0) { tgt[r] = bi; a.target_ids[r] = bi; }
+    if (lane == 0) { tgt[r] = bi; a.target_ids[r] = bi; }
   }
   __syncthreads();
   if (tid < a.B) {

@@ -150,26 +150,61 @@ verify_partial_generic_kernel(VerifyArgs a, SeqTable tab) {
 }
 
 // Combine: m = max_s m_s, l = sum_s l_s 2^(m_s - m), o = sum_s o_s 2^(m_s - m) / l.
-// One workgroup of D threads per (row, head).
+// One workgroup of 4 wavefronts per (row, head); wavefront w takes splits w, w+4, ..., four at a
+// time so that all its loads are in flight together; each lane owns D/64 consecutive elements.
 template <typename T, int D>
-__global__ void __launch_bounds__(D) verify_combine_kernel(VerifyArgs a, SeqTable tab) {
+__global__ void __launch_bounds__(256) verify_combine_kernel(VerifyArgs a, SeqTable tab) {
+  constexpr int EPL = D / 64;            // elements per lane: 1 or 2
+  __shared__ float red_m[4];
+  __shared__ float red_l[4];
+  __shared__ float red_o[4][D];
   const int row = blockIdx.x;           // b * n_q + i
   const int h = blockIdx.y;
   const int b = row / a.n_q, i = row % a.n_q;
   const int s0 = tab.cu_split[b], s1 = tab.cu_split[b + 1];
-  const int x = threadIdx.x;
+  const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int64_t rh = (int64_t)i * a.Hq + h;
+  const int64_t sstride = (int64_t)a.n_q * a.Hq;     // partial rows per split
+  // global max over the splits
   float m = kNegBig;
-  for (int s = s0; s < s1; ++s)
-    m = fmaxf(m, a.part_ml[(((int64_t)s * a.n_q + i) * a.Hq + h) * 2]);
-  float l = 0.f, o = 0.f;
-  for (int s = s0; s < s1; ++s) {
-    const int64_t idx = ((int64_t)s * a.n_q + i) * a.Hq + h;
-    const float w = fast_exp2(a.part_ml[idx * 2] - m);
-    l = fmaf(a.part_ml[idx * 2 + 1], w, l);
-    o = fmaf(a.part_o[idx * D + x], w, o);
+  for (int s = s0 + (int)threadIdx.x; s < s1; s += 256) m = fmaxf(m, a.part_ml[(s * sstride + rh) * 2]);
+  m = wave_max(m);
+  if (lane == 0) red_m[w] = m;
+  __syncthreads();
+  m = fmaxf(fmaxf(red_m[0], red_m[1]), fmaxf(red_m[2], red_m[3]));
+  float l = 0.f, o[EPL];
+#pragma unroll
+  for (int e = 0; e < EPL; ++e) o[e] = 0.f;
+  for (int sb = s0 + w; sb < s1; sb += 16) {
+    float ms[4], ls[4], ov[4][EPL];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int s = min(sb + 4 * u, s1 - 1);
+      const int64_t idx = s * sstride + rh;
+      ms[u] = a.part_ml[idx * 2];
+      ls[u] = a.part_ml[idx * 2 + 1];
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) ov[u][e] = a.part_o[idx * D + lane * EPL + e];
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const float wgt = (sb + 4 * u < s1) ? fast_exp2(ms[u] - m) : 0.f;
+      l = fmaf(ls[u], wgt, l);
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) o[e] = fmaf(ov[u][e], wgt, o[e]);
+    }
   }
-  Elem<T>::store((T *)a.out + ((int64_t)row * a.Hq + h) * D + x, o / l);
-  if (a.lse != nullptr && x == 0) a.lse[(int64_t)row * a.Hq + h] = (m + fast_log2(l)) * kLn2;
+  if (lane == 0) red_l[w] = l;
+#pragma unroll
+  for (int e = 0; e < EPL; ++e) red_o[w][lane * EPL + e] = o[e];
+  __syncthreads();
+  if (threadIdx.x < D) {
+    const int x = threadIdx.x;
+    const float lt = red_l[0] + red_l[1] + red_l[2] + red_l[3];
+    const float ot = red_o[0][x] + red_o[1][x] + red_o[2][x] + red_o[3][x];
+    Elem<T>::store((T *)a.out + ((int64_t)row * a.Hq + h) * D + x, ot / lt);
+    if (a.lse != nullptr && x == 0) a.lse[(int64_t)row * a.Hq + h] = (m + fast_log2(lt)) * kLn2;
+  }
 }
 
 template <typename T, int D>
@@ -192,7 +227,7 @@ hipError_t launch_verify_partial_generic(int dtype, const VerifyArgs &a, const S
 template <typename T, int D>
 static hipError_t launch_comb(const VerifyArgs &a, const SeqTable &tab, hipStream_t st) {
   dim3 grid(a.B * a.n_q, a.Hq);
-  hipLaunchKernelGGL((verify_combine_kernel<T, D>), grid, dim3(D), 0, st, a, tab);
+  hipLaunchKernelGGL((verify_combine_kernel<T, D>), grid, dim3(256), 0, st, a, tab);
   return hipGetLastError();
 }
 
