@@ -92,10 +92,19 @@ __global__ void __launch_bounds__(1024) accept_finalize_kernel(AcceptArgs a) {
     int bi = 0x7fffffff;
     const float *cv = a.cand_val + (int64_t)r * a.n_cand;
     const int32_t *ci = a.cand_idx + (int64_t)r * a.n_cand;
-    for (int c = lane; c < a.n_cand; c += 64) {
-      const float v = cv[c];
-      const int i = ci[c];
-      if (v > bv || (v == bv && i < bi)) { bv = v; bi = i; }
+    for (int c0 = lane; c0 < a.n_cand; c0 += 64 * 8) {   // eight independent loads in flight
+      float v[8];
+      int i[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const int c = c0 + 64 * u;
+        const bool in = c < a.n_cand;
+        v[u] = in ? cv[c] : -INFINITY;
+        i[u] = in ? ci[c] : 0x7fffffff;
+      }
+#pragma unroll
+      for (int u = 0; u < 8; ++u)
+        if (v[u] > bv || (v[u] == bv && i[u] < bi)) { bv = v[u]; bi = i[u]; }
     }
 #pragma unroll
     for (int o = 32; o >= 1; o >>= 1) {

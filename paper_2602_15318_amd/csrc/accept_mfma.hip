@@ -48,9 +48,16 @@ lm_head_mfma_kernel(AcceptArgs a, int row0) {
     const int qq = min(q, max(nq - 1, 0));
     const int j = qq / chunks_per_tile, cidx = qq - j * chunks_per_tile;
     const int v = min((gw + j * n_waves) * 16 + n, V - 1);
+#ifdef LM_EXP_LINEAR   // bandwidth experiment: same bytes, fully sequential per wavefront (wrong results)
+    const bf16_t *p = Wm + (int64_t)min((gw + j * n_waves) * 16, V - 16) * H + cidx * (512 * kLmChunk) + 8 * lane;
+#pragma unroll
+    for (int s = 0; s < kLmChunk; ++s) buf[s] = __builtin_nontemporal_load((const u32x4 *)(p + 512 * s));
+    (void)v;
+#else
     const bf16_t *p = Wm + (int64_t)v * H + cidx * (32 * kLmChunk) + 8 * c4;
 #pragma unroll
     for (int s = 0; s < kLmChunk; ++s) buf[s] = __builtin_nontemporal_load((const u32x4 *)(p + 32 * s));
+#endif
   };
   u32x4 bufA[kLmChunk], bufB[kLmChunk];
   issue(0, bufA);
@@ -114,6 +121,144 @@ lm_head_mfma_kernel(AcceptArgs a, int row0) {
   }
 }
 
+
+// ------------------------------------------------------------------------------------------------
+// k-split version, used when hidden = NW * 512 with NW <= 16 (3584 -> 7 wavefronts): the fast path.
+//
+// A workgroup of NW wavefronts owns groups of 64 consecutive vocabulary rows (4 MFMA tiles);
+// wavefront w owns the k-slice [512 w, 512 w + 512) of every row: its slice of the 16 hidden rows
+// lives in registers for the whole pass (16 B operands), and every load instruction of the
+// wavefront reads 1 KB that is contiguous in memory (the slice of one weight row), so the
+// workgroup as a whole sweeps 448 KB of W front to back.  The 16-row tile goes registers -> LDS
+// (private 16 KB per wavefront, XOR swizzled) -> A operands.  The wavefronts' partial logits of a
+// group are summed through LDS; wavefront g < 4 then owns the argmax bookkeeping of tile g.
+constexpr int kKsGroup = 4;               // vocabulary tiles (of 16 rows) per group
+
+template <int NW>
+__global__ void __launch_bounds__(NW * 64)
+lm_head_ksplit_kernel(AcceptArgs a, int row0) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  // [NW][16 KB] staging, then [NW][kKsGroup][64] f32x4 partial logits
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int n = lane & 15, c4 = lane >> 4;
+  const int H = a.H, V = a.V;
+  const bf16_t *Wm = (const bf16_t *)a.lm_head;
+  unsigned char *stg = smem + w * 16384;
+  f32x4 *red = reinterpret_cast<f32x4 *>(smem + NW * 16384);
+
+  const int n_groups = (V + 16 * kKsGroup - 1) / (16 * kKsGroup);
+  const int my_groups = n_groups > (int)blockIdx.x ? (n_groups - blockIdx.x + gridDim.x - 1) / gridDim.x : 0;
+  const int n_tiles = my_groups * kKsGroup;          // tiles this wavefront streams
+
+  // tile t of this workgroup -> first vocabulary row
+  auto tile_row0 = [&](int t) {
+    const int grp = blockIdx.x + (t / kKsGroup) * gridDim.x;
+    return (grp * kKsGroup + (t % kKsGroup)) * 16;
+  };
+  // 16 loads of 1 KB: load r = the k-slice of row r of the tile (rows clamped to the last row).
+  // Issued unconditionally (tile index clamped) so that the number of loads in flight is static.
+  u32x4 buf[16];
+  auto issue = [&](int t) {
+    const int v0 = tile_row0(min(t, max(n_tiles - 1, 0)));
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int v = min(v0 + r, V - 1);
+      buf[r] = __builtin_nontemporal_load((const u32x4 *)(Wm + (int64_t)v * H + 512 * w + 8 * lane));
+    }
+  };
+  issue(0);
+
+  // B operands: lane (n, c4) holds hidden[row0 + n][512 w + 32 ks + 8 c4 .. +8], ks = 0..15
+  bf16x8 hreg[16];
+  {
+    const bool ok = row0 + n < a.M;
+    const bf16_t *hp = (const bf16_t *)a.hidden + (int64_t)(ok ? row0 + n : 0) * H + 512 * w + 8 * c4;
+#pragma unroll
+    for (int ks = 0; ks < 16; ++ks) {
+      u32x4 v = *(const u32x4 *)(hp + 32 * ks);
+      if (!ok) v = (u32x4){0u, 0u, 0u, 0u};
+      hreg[ks] = __builtin_bit_cast(bf16x8, v);
+    }
+  }
+
+  // staging: lane i of load r holds chunk i (16 bytes) of row r; stored at chunk position
+  // (i & ~15) | ((i & 15) ^ r) so that the A-operand reads (16 rows, same chunk) hit all banks
+  const int a_base = n * 1024;      // A read: row n, chunk 4 ks + c4
+  float best = -INFINITY;
+  int best_i = 0x7fffffff;
+  f32x4 part[kKsGroup];
+
+  for (int t = 0; t < n_tiles; ++t) {
+#pragma unroll
+    for (int r = 0; r < 16; ++r)
+      *reinterpret_cast<u32x4 *>(stg + r * 1024 + (((lane & ~15) | ((lane & 15) ^ r)) << 4)) = buf[r];
+    issue(t + 1);
+    f32x4 acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int ks = 0; ks < 16; ks += 2) {
+      const int ch0 = 4 * ks + c4, ch1 = ch0 + 4;
+      const bf16x8 a0 = *reinterpret_cast<const bf16x8 *>(stg + a_base + (((ch0 & ~15) | ((ch0 & 15) ^ n)) << 4));
+      const bf16x8 a1 = *reinterpret_cast<const bf16x8 *>(stg + a_base + (((ch1 & ~15) | ((ch1 & 15) ^ n)) << 4));
+      acc0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0, hreg[ks], acc0, 0, 0, 0);
+      acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, hreg[ks + 1], acc1, 0, 0, 0);
+    }
+    const int g = t % kKsGroup;
+    // static register index for part[]
+#pragma unroll
+    for (int gg = 0; gg < kKsGroup; ++gg)
+      if (gg == g) part[gg] = acc0 + acc1;
+    if (g == kKsGroup - 1) {
+      // sum the group's partial logits over the wavefronts
+      f32x4 *rb = red;
+#pragma unroll
+      for (int gg = 0; gg < kKsGroup; ++gg) rb[(w * kKsGroup + gg) * 64 + lane] = part[gg];
+      __syncthreads();
+      if (w < kKsGroup) {
+        f32x4 sum = rb[(0 * kKsGroup + w) * 64 + lane];
+#pragma unroll
+        for (int ww = 1; ww < NW; ++ww) sum += rb[(ww * kKsGroup + w) * 64 + lane];
+        const int vbase = tile_row0(t - (kKsGroup - 1) + w) + 4 * c4;
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+          if (vbase + i < V && sum[i] > best) { best = sum[i]; best_i = vbase + i; }
+      }
+      __syncthreads();   // reads done before the next group's partials are written
+    }
+  }
+
+  // candidates: wavefronts 0..3 hold, per lane, the best of tiles g = w over all groups
+  if (w < kKsGroup) {
+#pragma unroll
+    for (int o = 16; o <= 32; o <<= 1) {
+      const float ov = __shfl_xor(best, o, 64);
+      const int oi = __shfl_xor(best_i, o, 64);
+      if (ov > best || (ov == best && oi < best_i)) { best = ov; best_i = oi; }
+    }
+    if (c4 == 0 && row0 + n < a.M) {
+      const int slot = blockIdx.x * kKsGroup + w;
+      a.cand_val[(int64_t)(row0 + n) * a.n_cand + slot] = best;
+      a.cand_idx[(int64_t)(row0 + n) * a.n_cand + slot] = best_i;
+    }
+  }
+}
+
+template <int NW>
+hipError_t launch_ksplit(const AcceptArgs &a, hipStream_t st) {
+  const int lds = NW * 16384 + NW * kKsGroup * 64 * 16;
+  static const hipError_t attr = hipFuncSetAttribute(
+      (const void *)lm_head_ksplit_kernel<NW>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+  if (attr != hipSuccess) return attr;
+  for (int row0 = 0; row0 < a.M; row0 += 16) {
+    hipLaunchKernelGGL((lm_head_ksplit_kernel<NW>), dim3(kLmBlocks), dim3(NW * 64), lds, st, a, row0);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
+  return hipSuccess;
+}
+
+bool ksplit_ok(int H) { return H == 3584 || H == 4096; }
+
 }  // namespace
 
 bool lm_head_mfma_supported(int dtype, int M, int H, int V) {
@@ -122,9 +267,13 @@ bool lm_head_mfma_supported(int dtype, int M, int H, int V) {
   return dtype == SPARROW_BF16 && H % (32 * kLmChunk) == 0 && 16 * H * 2 <= 144 * 1024;
 }
 
-int accept_num_candidates(int, int, int, int) { return kLmBlocks * kLmWaves; }
+int accept_num_candidates(int, int, int H, int) {
+  return ksplit_ok(H) ? kLmBlocks * kKsGroup : kLmBlocks * kLmWaves;
+}
 
 hipError_t launch_lm_head_mfma(const AcceptArgs &a, hipStream_t st) {
+  if (a.H == 3584) return launch_ksplit<7>(a, st);
+  if (a.H == 4096) return launch_ksplit<8>(a, st);
   const int lds = 16 * a.H * 2;
   static const hipError_t attr = hipFuncSetAttribute(
       (const void *)lm_head_mfma_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 144 * 1024);
