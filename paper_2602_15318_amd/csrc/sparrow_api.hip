@@ -74,9 +74,25 @@ bool use_mfma_verify(const sparrow_attn_desc *d) {
   return verify_partial_mfma_supported(d->dtype, d->head_dim);
 }
 
+// Workspace split: partial outputs first, then (max, sum) pairs, each rounded up to 256 bytes.
+void verify_ws_layout(const sparrow_attn_desc *d, int64_t slots, int32_t n_q, bool mfma,
+                      size_t *bytes_o, size_t *bytes_ml) {
+  if (mfma) {
+    const int R = n_q * (d->n_q_heads / d->n_kv_heads);
+    const size_t units = (size_t)slots * d->n_kv_heads * ((R + 63) / 64);
+    *bytes_o = round_up(units * verify_mfma_unit_floats_o() * sizeof(float), 256);
+    *bytes_ml = round_up(units * verify_mfma_unit_floats_ml() * sizeof(float), 256);
+  } else {
+    const size_t rows = (size_t)slots * n_q * d->n_q_heads;
+    *bytes_o = round_up(rows * d->head_dim * sizeof(float), 256);
+    *bytes_ml = round_up(rows * 2 * sizeof(float), 256);
+  }
+}
+
 size_t verify_ws_bytes(const sparrow_attn_desc *d, int64_t max_slots, int32_t n_q) {
-  const size_t rows = (size_t)max_slots * n_q * d->n_q_heads;
-  return round_up(rows * d->head_dim * sizeof(float), 256) + round_up(rows * 2 * sizeof(float), 256);
+  size_t bo, bml;
+  verify_ws_layout(d, max_slots, n_q, use_mfma_verify(d), &bo, &bml);
+  return bo + bml;
 }
 }  // namespace
 }  // namespace sparrow
@@ -184,15 +200,16 @@ int sparrow_verify_attn(const sparrow_attn_desc *desc, const void *q, const void
   a.chunk = chunk; a.n_slots = n_slots;
   a.scale_log2 = scale_log2_of(desc);
   a.stride_tok = desc->kv_stride_token; a.stride_head = desc->kv_stride_head;
-  const size_t rows = (size_t)n_slots * n_q * desc->n_q_heads;
+  size_t bytes_o, bytes_ml;
+  verify_ws_layout(desc, n_slots, n_q, mfma, &bytes_o, &bytes_ml);
   a.part_o = (float *)workspace;
-  a.part_ml = (float *)((char *)workspace + round_up(rows * desc->head_dim * sizeof(float), 256));
+  a.part_ml = (float *)((char *)workspace + bytes_o);
   a.out = out; a.lse = lse;
   hipStream_t st = (hipStream_t)hip_stream;
   hipError_t e = mfma ? launch_verify_partial_mfma(a, tab, st)
                       : launch_verify_partial_generic(desc->dtype, a, tab, st);
   if (e != hipSuccess) return fail(SPARROW_ERR_DEVICE, "verify partial launch: %s", hipGetErrorString(e));
-  e = launch_verify_combine(desc->dtype, a, tab, st);
+  e = mfma ? launch_verify_combine_mfma(a, tab, st) : launch_verify_combine(desc->dtype, a, tab, st);
   if (e != hipSuccess) return fail(SPARROW_ERR_DEVICE, "verify combine launch: %s", hipGetErrorString(e));
   return SPARROW_OK;
 }

@@ -23,8 +23,10 @@ struct VerifyArgs {
   int32_t n_slots;        // cu_split[B]
   float scale_log2;       // softmax scale * log2(e)
   int64_t stride_tok, stride_head;
-  float *part_o;          // [n_slots, n_q, Hq, d]   unnormalised partial outputs
-  float *part_ml;         // [n_slots, n_q, Hq, 2]   running max (log2 domain), partial sum
+  // plain-ALU path: part_o [n_slots, n_q, Hq, d], part_ml [n_slots, n_q, Hq, 2];
+  // matrix-core path: tiled per (split, KV head, row block), see verify_attn_mfma.hip
+  float *part_o;          // unnormalised partial outputs
+  float *part_ml;         // running max (log2 domain), partial sum
   void *out;              // [B*n_q, Hq, d]
   float *lse;             // [B*n_q, Hq] or nullptr
 };
@@ -42,6 +44,11 @@ hipError_t launch_verify_partial_generic(int dtype, const VerifyArgs &a, const S
 // Partial pass, matrix-core version: bf16, head_dim 128.
 bool verify_partial_mfma_supported(int dtype, int head_dim);
 hipError_t launch_verify_partial_mfma(const VerifyArgs &a, const SeqTable &tab, hipStream_t st);
+// Its partials use a tiled layout of their own: workspace floats per (split, KV head, block of 64
+// rows) unit, and the matching combine pass.
+int64_t verify_mfma_unit_floats_o();
+int64_t verify_mfma_unit_floats_ml();
+hipError_t launch_verify_combine_mfma(const VerifyArgs &a, const SeqTable &tab, hipStream_t st);
 // Second pass: merge the per-split partials of every (row, head).
 hipError_t launch_verify_combine(int dtype, const VerifyArgs &a, const SeqTable &tab,
                                  hipStream_t st);

@@ -19,9 +19,6 @@
 // The online-softmax state (m, l) and the rescale factor are per lane (= per query row).
 #include "common.hpp"
 #include "verify_attn.hpp"
-#ifndef SPARROW_EXP
-#define SPARROW_EXP 0
-#endif
 
 namespace sparrow {
 
@@ -30,7 +27,7 @@ namespace {
 constexpr int kTile = 32;                 // tokens per tile
 constexpr int kRowBytes = 256;            // one K or V row of a head: 128 bf16
 constexpr int kTileBytes = kTile * kRowBytes;
-constexpr int kPrefetch = 3;              // tiles per stream in flight in registers
+constexpr int kSub = 1;                   // 32-token tiles per stream per step
 constexpr int kRowsPerWG = 64;
 constexpr int kStreams = 2;
 
@@ -62,18 +59,20 @@ __device__ __forceinline__ float quad_sum(float v) {
   return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
 
+// kPrefetch = steps in flight in registers.  The whole split of a workgroup is only a handful of
+// steps at decode-time sizes (7 at 26k context on 256 compute units), so a deep look-ahead turns
+// the kernel into "load most of it, then compute": depth 1 is fastest there, depth 2 once the
+// splits get long (batches, very long contexts).
+template <int kPrefetch>
 __global__ void __launch_bounds__(256 * kStreams)
 verify_partial_mfma_kernel(VerifyArgs a, SeqTable tab) {
-  // [stream][buf][K,V]; after the main loop the first 32 KB + 2 KB are reused for the stream merge
-  __shared__ __attribute__((aligned(16))) unsigned char lds[kStreams][2][2][kTileBytes];
+  // [stream][buf][K,V][kSub tiles]; after the main loop the first 34 KB are reused for the merge
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+  constexpr int kStepBytes = kSub * kTileBytes;            // K (or V) rows of one stream step
+  auto lds_at = [&](int strm_, int buf, int kv) {
+    return lds + ((strm_ * 2 + buf) * 2 + kv) * kStepBytes;
+  };
 
-#ifdef SPARROW_TRACE
-  long long tr[40]; int ntr = 0;
-#define TR() do { if (ntr < 40) tr[ntr++] = wall_clock64(); } while (0)
-#else
-#define TR() do {} while (0)
-#endif
-  TR();
   const int tid = threadIdx.x & 255, strm = threadIdx.x >> 8;
   const int w = tid >> 6, lane = tid & 63;
   const int n = lane & 15, c4 = lane >> 4;
@@ -85,8 +84,8 @@ verify_partial_mfma_kernel(VerifyArgs a, SeqTable tab) {
   const int L = len - a.n_q;
   const int t0 = (slot - tab.cu_split[b]) * a.chunk;
   const int t1 = min(len, t0 + a.chunk);
-  const int n_tiles = (t1 - t0 + kTile - 1) / kTile;          // of the workgroup
-  const int n_pairs = (n_tiles + kStreams - 1) / kStreams;    // loop trips, same for both streams
+  const int n_tiles = (t1 - t0 + kTile - 1) / kTile;                    // of the workgroup
+  const int n_steps = (n_tiles + kStreams * kSub - 1) / (kStreams * kSub);   // loop trips
   const int64_t tok_base = tab.cu_len[b];
   const bf16_t *Kg = (const bf16_t *)a.k + c * a.stride_head;
   const bf16_t *Vg = (const bf16_t *)a.v + c * a.stride_head;
@@ -98,44 +97,56 @@ verify_partial_mfma_kernel(VerifyArgs a, SeqTable tab) {
   const int i_row = row_ok ? rho / g : 0;
   const int h = row_ok ? c * g + rho % g : 0;
 
-  // ---- tile loader: thread -> rows (tid/16) and (tid/16 + 16), 16-byte chunk tid%16
+  // ---- loader: in step `st` stream `strm` owns tiles (st*kStreams + strm)*kSub .. +kSub, i.e.
+  // 32*kSub consecutive tokens; thread -> rows tid/16 + 16 j, 16-byte chunk tid%16.  Rows past
+  // the end of the split are clamped to its last token (loaded, never used), so every load is
+  // unconditional and the number of loads in flight is a compile-time constant at every wait.
   const int ld_row = tid >> 4, ld_ch = tid & 15;
-  u32x4 stage[kPrefetch][4];
-  auto issue = [&](int tile, u32x4 *st) {   // tile: index within the workgroup's split
-    const int tb = t0 + tile * kTile;
-    const int ra = min(tb + ld_row, t1 - 1), rb2 = min(tb + ld_row + 16, t1 - 1);
-    const int64_t oa = (tok_base + ra) * a.stride_tok + ld_ch * 8;
-    const int64_t ob = (tok_base + rb2) * a.stride_tok + ld_ch * 8;
-    st[0] = __builtin_nontemporal_load((const u32x4 *)(Kg + oa));
-    st[1] = __builtin_nontemporal_load((const u32x4 *)(Kg + ob));
-    st[2] = __builtin_nontemporal_load((const u32x4 *)(Vg + oa));
-    st[3] = __builtin_nontemporal_load((const u32x4 *)(Vg + ob));
+  constexpr int kLd = 2 * kSub;                       // 16-row slabs per step (per K and per V)
+  u32x4 stage[kPrefetch][2 * kLd];
+  auto issue = [&](int st, u32x4 *sg) {
+    const int tb = t0 + (st * kStreams + strm) * kSub * kTile;
+#pragma unroll
+    for (int j = 0; j < kLd; ++j) {
+      const int r = min(tb + ld_row + 16 * j, t1 - 1);
+      const int64_t o = (tok_base + r) * a.stride_tok + ld_ch * 8;
+      sg[j] = __builtin_nontemporal_load((const u32x4 *)(Kg + o));
+      sg[kLd + j] = __builtin_nontemporal_load((const u32x4 *)(Vg + o));
+    }
   };
-  const int st_off_a = ld_row * kRowBytes + ((ld_ch ^ swz(ld_row)) << 4);
-  const int st_off_b = st_off_a + 16 * kRowBytes;   // row + 16 has the same swizzle
-  auto stash = [&](int buf, const u32x4 *st) {
-    *reinterpret_cast<u32x4 *>(&lds[strm][buf][0][st_off_a]) = st[0];
-    *reinterpret_cast<u32x4 *>(&lds[strm][buf][0][st_off_b]) = st[1];
-    *reinterpret_cast<u32x4 *>(&lds[strm][buf][1][st_off_a]) = st[2];
-    *reinterpret_cast<u32x4 *>(&lds[strm][buf][1][st_off_b]) = st[3];
+  // row r of the step lands at byte r*256 + ((chunk ^ swz(r)) * 16); swz depends on r mod 16 only
+  const int st_off = ld_row * kRowBytes + ((ld_ch ^ swz(ld_row)) << 4);
+  auto stash = [&](int buf, const u32x4 *sg) {
+    unsigned char *kb = lds_at(strm, buf, 0), *vb = lds_at(strm, buf, 1);
+#pragma unroll
+    for (int j = 0; j < kLd; ++j) {
+      *reinterpret_cast<u32x4 *>(kb + st_off + 16 * j * kRowBytes) = sg[j];
+      *reinterpret_cast<u32x4 *>(vb + st_off + 16 * j * kRowBytes) = sg[kLd + j];
+    }
   };
 
-  // ---- Q^T operand (B of the score MFMA): lane (n, c4) holds Q[row][32*ks + 8*c4 .. +8]
+  // ---- first step, then Q^T (B operand of the score MFMA: lane (n, c4) holds
+  // Q[row][32*ks + 8*c4 .. +8]), then the rest of the look-ahead.
   bf16x8 qreg[4];
   {
+    issue(0, stage[0]);
     const int64_t qrow = row_ok ? ((int64_t)b * a.n_q + i_row) * a.Hq + h : 0;   // clamped, zeroed below
     const bf16_t *qp = (const bf16_t *)a.q + qrow * 128 + 8 * c4;
     u32x4 qv[4];
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) qv[ks] = *(const u32x4 *)(qp + 32 * ks);
-    // Every vector-memory operation from here to the end of the main loop is unconditional, so
-    // the number of loads in flight is a compile-time constant at every wait.
+    // The memory pipeline of a compute unit serves requests in issue order and a wavefront
+    // issues all its loads back to back: without this barrier the look-ahead of the wavefronts
+    // that issue first would queue ahead of the FIRST step of the others (measured: 3 us of
+    // skew between the two streams).
+    __syncthreads();
 #pragma unroll
-    for (int p = 0; p < kPrefetch; ++p) issue(kStreams * p + strm, stage[p]);
-    // Q was requested before the 4*kPrefetch tile loads and loads retire in order: wait until at
-    // most those are outstanding (vmcnt = 12, no wait on the other counters).
-    static_assert(kPrefetch == 3, "the immediate below encodes vmcnt(4 * kPrefetch)");
-    __builtin_amdgcn_s_waitcnt(0x0F7C);
+    for (int p = 1; p < kPrefetch; ++p) issue(p, stage[p]);
+    // Loads retire in order: Q (and the first step before it) have landed once at most the
+    // loads issued after Q are outstanding (other counters untouched).
+    constexpr int kAfterQ = (kPrefetch - 1) * 2 * kLd;
+    static_assert(kAfterQ < 64, "vmcnt is a 6-bit counter");
+    __builtin_amdgcn_s_waitcnt(0x0F70 | (kAfterQ & 15) | ((kAfterQ >> 4) << 14));
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) {
       if (!row_ok) qv[ks] = (u32x4){0u, 0u, 0u, 0u};
@@ -146,12 +157,11 @@ verify_partial_mfma_kernel(VerifyArgs a, SeqTable tab) {
   unsigned long long anc = 0ull;
   if (row_ok && t1 > L) anc = ancestor_mask(a.parent, i_row);
 
-  TR();
   // LDS read offsets
-  const int k_off = n * kRowBytes;                 // + subtile*16 rows, chunk (4*ks + c4) ^ swz(n)
+  const int k_off = n * kRowBytes;                 // + 16-row slab, chunk (4*ks + c4) ^ swz(n)
   const int k_swz = swz(n);
   const int s16 = lane & 15;                       // source lane index within the 16-lane group
-  const int v_row = 4 * c4 + (s16 >> 2);           // token within a 16-token sub-tile
+  const int v_row = 4 * c4 + (s16 >> 2);           // token within a 16-token slab
   const int v_swz = swz(v_row);
   const int v_off = v_row * kRowBytes + ((s16 & 1) << 3);   // + chunk (2*mt + ((s16>>1)&1)) ^ swz
   const int v_chb = (s16 >> 1) & 1;
@@ -161,40 +171,33 @@ verify_partial_mfma_kernel(VerifyArgs a, SeqTable tab) {
 #pragma unroll
   for (int mt = 0; mt < 8; ++mt) o_acc[mt] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
-  auto compute = [&](int tile, int buf) {
-    const unsigned char *Ks = &lds[strm][buf][0][0];
-    const unsigned char *Vs = &lds[strm][buf][1][0];
-    const int tb = t0 + tile * kTile;
-    // all LDS reads of the tile are issued up front: K operands first, V operands land while the
-    // scores and the softmax are computed
-    bf16x8 ka[2][4];
+  // One step of one stream: 32*kSub tokens against the wavefront's 16 rows, one joint softmax
+  // update (a single running-max / rescale for the whole step).
+  auto compute = [&](int st, int buf) {
+    const unsigned char *Ks = lds_at(strm, buf, 0);
+    const unsigned char *Vs = lds_at(strm, buf, 1);
+    const int tb = t0 + (st * kStreams + strm) * kSub * kTile;
+    f32x4 s[kLd];
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+    for (int j = 0; j < kLd; ++j) {
+      bf16x8 ka[4];
 #pragma unroll
       for (int ks = 0; ks < 4; ++ks)
-        ka[j][ks] = lds_read_b128(Ks + j * 16 * kRowBytes + k_off + (((4 * ks + c4) ^ k_swz) << 4));
-    bf16x4 va[8], vb[8];
+        ka[ks] = lds_read_b128(Ks + j * 16 * kRowBytes + k_off + (((4 * ks + c4) ^ k_swz) << 4));
+      s[j] = (f32x4){0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int mt = 0; mt < 8; ++mt) {
-      const int ch = ((2 * mt + v_chb) ^ v_swz) << 4;
-      va[mt] = lds_read_tr(Vs + v_off + ch);
-      vb[mt] = lds_read_tr(Vs + 16 * kRowBytes + v_off + ch);
-    }
-    f32x4 s[2] = {(f32x4){0.f, 0.f, 0.f, 0.f}, (f32x4){0.f, 0.f, 0.f, 0.f}};
-#pragma unroll
-    for (int ks = 0; ks < 4; ++ks) {
-      s[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[0][ks], qreg[ks], s[0], 0, 0, 0);
-      s[1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[1][ks], qreg[ks], s[1], 0, 0, 0);
+      for (int ks = 0; ks < 4; ++ks)
+        s[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[ks], qreg[ks], s[j], 0, 0, 0);
     }
     // scale, mask, online softmax (per lane = per query row)
-    float sc[8];
+    float sc[4 * kLd];
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+    for (int j = 0; j < kLd; ++j)
 #pragma unroll
       for (int i = 0; i < 4; ++i) sc[4 * j + i] = s[j][i] * a.scale_log2;
-    if (tb + kTile > min(t1, L)) {   // wavefront-uniform: tile touches the split end or draft rows
+    if (tb + kSub * kTile > min(t1, L)) {   // wavefront-uniform: step touches the split end or draft rows
 #pragma unroll
-      for (int j = 0; j < 2; ++j)
+      for (int j = 0; j < kLd; ++j)
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
           const int tok = tb + 16 * j + 4 * c4 + i;
@@ -203,57 +206,71 @@ verify_partial_mfma_kernel(VerifyArgs a, SeqTable tab) {
           sc[4 * j + i] = ((tok < t1) & vis) ? sc[4 * j + i] : -INFINITY;
         }
     }
-    float mx = fmaxf(fmaxf(fmaxf(sc[0], sc[1]), fmaxf(sc[2], sc[3])),
-                     fmaxf(fmaxf(sc[4], sc[5]), fmaxf(sc[6], sc[7])));
+    float mx = sc[0];
+#pragma unroll
+    for (int e = 1; e < 4 * kLd; ++e) mx = fmaxf(mx, sc[e]);
     mx = quad_max(mx);
     const float m_new = fmaxf(m_run, mx);
     const float alpha = fast_exp2(m_run - m_new);
     m_run = m_new;
     float psum = 0.f;
-    bf16x8 pb;
+    bf16x8 pb[kSub];
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      const float p = fast_exp2(sc[e] - m_new);
-      psum += p;
-      pb[e] = (__bf16)p;
-    }
+    for (int u = 0; u < kSub; ++u)
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const float p = fast_exp2(sc[8 * u + e] - m_new);
+        psum += p;
+        pb[u][e] = (__bf16)p;
+      }
     l_run = l_run * alpha + psum;
 #pragma unroll
     for (int mt = 0; mt < 8; ++mt) {
       o_acc[mt] *= alpha;
-      const bf16x8 vt = __builtin_shufflevector(va[mt], vb[mt], 0, 1, 2, 3, 4, 5, 6, 7);
-      o_acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vt, pb, o_acc[mt], 0, 0, 0);
+      const int ch = ((2 * mt + v_chb) ^ v_swz) << 4;
+#pragma unroll
+      for (int u = 0; u < kSub; ++u) {
+        const bf16x4 va = lds_read_tr(Vs + (2 * u) * 16 * kRowBytes + v_off + ch);
+        const bf16x4 vb = lds_read_tr(Vs + (2 * u + 1) * 16 * kRowBytes + v_off + ch);
+        const bf16x8 vt = __builtin_shufflevector(va, vb, 0, 1, 2, 3, 4, 5, 6, 7);
+        o_acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vt, pb[u], o_acc[mt], 0, 0, 0);
+      }
     }
   };
 
-  // ---- main loop: unrolled by the prefetch depth so the staging registers are static.  Loads and
-  // LDS stores also run for tiles past the end of the split (rows clamped to the last token, data
-  // unused); only the compute is skipped for them.
-  for (int base = 0; base < n_pairs; base += kPrefetch) {
+  // ---- main loop, unrolled by the prefetch depth so that the staging registers are static.
+  // Look-ahead loads past the end of the split are clamped duplicates of its last rows.
+  int base = 0;
+  for (; base + kPrefetch <= n_steps; base += kPrefetch) {
 #pragma unroll
     for (int p = 0; p < kPrefetch; ++p) {
-      const int pair = base + p;
-      const int tile = kStreams * pair + strm;
-      const int buf = pair & 1;
-#ifndef SPARROW_EXP
-#define SPARROW_EXP 0
-#endif
-      if (!(SPARROW_EXP & 2)) stash(buf, stage[p]);
-      if (!(SPARROW_EXP & 4)) issue(tile + kStreams * kPrefetch, stage[p]);
-      TR();
+      const int st = base + p;
+      const int buf = st & 1;
+      stash(buf, stage[p]);
+      issue(st + kPrefetch, stage[p]);
       __syncthreads();
-      TR();
-      if (!(SPARROW_EXP & 1)) if (tile < n_tiles && wave_active) compute(tile, buf);
-      TR();
+      if ((st * kStreams + strm) * kSub < n_tiles && wave_active) compute(st, buf);
+    }
+  }
+  // remainder (n_steps % kPrefetch trips): everything it needs is already in flight
+#pragma unroll
+  for (int p = 0; p < kPrefetch - 1; ++p) {
+    const int st = base + p;
+    if (st < n_steps) {                    // uniform over the workgroup
+      const int buf = st & 1;
+      stash(buf, stage[p]);
+      __syncthreads();
+      if ((st * kStreams + strm) * kSub < n_tiles && wave_active) compute(st, buf);
     }
   }
 
-  TR();
-  // ---- merge the two streams (stream 1 -> LDS -> stream 0) and write the split's partials
+  // ---- merge the two streams (stream 1 -> LDS -> stream 0) and write the split's partials in
+  // register layout: [slot][kv head][row block][wavefront][mt][lane] x 4 floats, so that every
+  // store instruction writes 1 KB of contiguous memory.
   l_run = quad_sum(l_run);
   __syncthreads();                      // all tile reads done: LDS is free
-  f32x4 *mo = reinterpret_cast<f32x4 *>(&lds[0][0][0][0]);           // [w][mt][lane]
-  float *mm = reinterpret_cast<float *>(&lds[0][0][0][0] + 4 * 8 * 64 * 16);   // [w][lane][m,l]
+  f32x4 *mo = reinterpret_cast<f32x4 *>(lds);                                  // [w][mt][lane]
+  float *mm = reinterpret_cast<float *>(lds + 4 * 8 * 64 * 16);                // [w][lane][m,l]
   if (strm == 1) {
 #pragma unroll
     for (int mt = 0; mt < 8; ++mt) mo[(w * 8 + mt) * 64 + lane] = o_acc[mt];
@@ -261,31 +278,101 @@ verify_partial_mfma_kernel(VerifyArgs a, SeqTable tab) {
     mm[(w * 64 + lane) * 2 + 1] = l_run;
   }
   __syncthreads();
-  if (strm == 0 && row_ok) {
+  if (strm == 0 && wave_active) {
     const float m1 = mm[(w * 64 + lane) * 2], l1 = mm[(w * 64 + lane) * 2 + 1];
     const float m_new = fmaxf(m_run, m1);
     const float a0 = fast_exp2(m_run - m_new), a1 = fast_exp2(m1 - m_new);
-    const int64_t pidx = ((int64_t)slot * a.n_q + i_row) * a.Hq + h;
-    float *po = a.part_o + pidx * 128 + 4 * c4;
+    const int64_t unit = ((int64_t)slot * a.Hkv + c) * gridDim.z + rb;       // (split, head, row block)
+    f32x4 *po = reinterpret_cast<f32x4 *>(a.part_o) + (unit * 4 + w) * (8 * 64) + lane;
 #pragma unroll
     for (int mt = 0; mt < 8; ++mt) {
       const f32x4 o1 = mo[(w * 8 + mt) * 64 + lane];
-      *reinterpret_cast<f32x4 *>(po + 16 * mt) = o_acc[mt] * a0 + o1 * a1;
+      po[mt * 64] = o_acc[mt] * a0 + o1 * a1;
     }
     if (c4 == 0) {
-      a.part_ml[pidx * 2] = m_new;
-      a.part_ml[pidx * 2 + 1] = l_run * a0 + l1 * a1;
+      float *pml = a.part_ml + (unit * kRowsPerWG + 16 * w + n) * 2;
+      pml[0] = m_new;
+      pml[1] = l_run * a0 + l1 * a1;
     }
   }
-  TR();
-#ifdef SPARROW_TRACE
-  if (a.lse && (threadIdx.x & 63) == 0 && blockIdx.y == 0 && (blockIdx.x == 0 || blockIdx.x == 30)) {
-    long long *dst = (long long *)a.lse + ((blockIdx.x ? 1 : 0) * 8 + (threadIdx.x >> 6)) * 40;
-    for (int i = 0; i < 40; ++i) dst[i] = i < ntr ? tr[i] : 0;
-  }
-#endif
 }
 
+// Combine for the tiled partial layout above.  One workgroup (4 wavefronts) per (sequence, KV head,
+// 16-row tile, pair of 16-wide d tiles); wavefront ws merges splits ws, ws+4, ... (four splits in
+// flight at a time, 2 KB contiguous per split), the four running results are merged through LDS.
+__global__ void __launch_bounds__(256)
+verify_combine_tiled_kernel(VerifyArgs a, SeqTable tab, int rbs) {
+  __shared__ f32x4 xo[4][2][64];
+  __shared__ float xm[4][64], xl[4][64];
+  const int unit_in_seq = blockIdx.x;            // (c * rbs + rb) * 4 + w
+  const int wq = unit_in_seq & 3, crb = unit_in_seq >> 2;
+  const int rb = crb % rbs, c = crb / rbs;
+  const int mt0 = 2 * blockIdx.y;
+  const int b = blockIdx.z;
+  const int ws = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int n = lane & 15, c4 = lane >> 4;
+  const int g = a.Hq / a.Hkv, R = a.n_q * g;
+  if (rb * kRowsPerWG + 16 * wq >= R) return;    // tile without rows (uniform)
+  const int s0 = tab.cu_split[b], s1 = tab.cu_split[b + 1];
+  const f32x4 *po = reinterpret_cast<const f32x4 *>(a.part_o);
+  float m_run = kNegBig, l_run = 0.f;
+  f32x4 o0 = {0.f, 0.f, 0.f, 0.f}, o1 = {0.f, 0.f, 0.f, 0.f};
+  for (int sb = s0 + ws; sb < s1; sb += 16) {
+    float ms[4], ls[4];
+    f32x4 pa[4], pb[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int s = min(sb + 4 * u, s1 - 1);
+      const int64_t unit = ((int64_t)s * a.Hkv + c) * rbs + rb;
+      const float *pml = a.part_ml + (unit * kRowsPerWG + 16 * wq + n) * 2;
+      ms[u] = pml[0];
+      ls[u] = pml[1];
+      const f32x4 *p = po + ((unit * 4 + wq) * 8 + mt0) * 64 + lane;
+      pa[u] = p[0];
+      pb[u] = p[64];
+    }
+    float mx = m_run;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) if (sb + 4 * u < s1) mx = fmaxf(mx, ms[u]);
+    const float alpha = fast_exp2(m_run - mx);
+    m_run = mx;
+    l_run *= alpha; o0 *= alpha; o1 *= alpha;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const float wgt = (sb + 4 * u < s1) ? fast_exp2(ms[u] - mx) : 0.f;
+      l_run = fmaf(ls[u], wgt, l_run);
+      o0 += pa[u] * wgt;
+      o1 += pb[u] * wgt;
+    }
+  }
+  xo[ws][0][lane] = o0; xo[ws][1][lane] = o1;
+  xm[ws][lane] = m_run; xl[ws][lane] = l_run;
+  __syncthreads();
+  if (ws == 0) {
+    float m = fmaxf(fmaxf(xm[0][lane], xm[1][lane]), fmaxf(xm[2][lane], xm[3][lane]));
+    float l = 0.f;
+    f32x4 r0 = {0.f, 0.f, 0.f, 0.f}, r1 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const float wgt = fast_exp2(xm[k][lane] - m);
+      l = fmaf(xl[k][lane], wgt, l);
+      r0 += xo[k][0][lane] * wgt;
+      r1 += xo[k][1][lane] * wgt;
+    }
+    const int rho = rb * kRowsPerWG + 16 * wq + n;
+    if (rho < R) {
+      const int i_row = rho / g, h = c * g + rho % g;
+      const int64_t orow = ((int64_t)b * a.n_q + i_row) * a.Hq + h;
+      const float inv = 1.0f / l;
+      bf16_t *out = (bf16_t *)a.out + orow * 128 + 16 * mt0 + 4 * c4;
+      u32x2 w0 = {pack_bf16x2(r0[0] * inv, r0[1] * inv), pack_bf16x2(r0[2] * inv, r0[3] * inv)};
+      u32x2 w1 = {pack_bf16x2(r1[0] * inv, r1[1] * inv), pack_bf16x2(r1[2] * inv, r1[3] * inv)};
+      *reinterpret_cast<u32x2 *>(out) = w0;
+      *reinterpret_cast<u32x2 *>(out + 16) = w1;
+      if (a.lse != nullptr && mt0 == 0 && c4 == 0) a.lse[orow] = (m + fast_log2(l)) * kLn2;
+    }
+  }
+}
 
 }  // namespace
 
@@ -293,10 +380,28 @@ bool verify_partial_mfma_supported(int dtype, int head_dim) {
   return dtype == SPARROW_BF16 && head_dim == 128;
 }
 
+// Floats of workspace per (split, KV head, row block) unit of the tiled partial layout.
+int64_t verify_mfma_unit_floats_o() { return 4 * 8 * 64 * 4; }
+int64_t verify_mfma_unit_floats_ml() { return kRowsPerWG * 2; }
+
 hipError_t launch_verify_partial_mfma(const VerifyArgs &a, const SeqTable &tab, hipStream_t st) {
   const int R = a.n_q * (a.Hq / a.Hkv);
   dim3 grid(a.n_slots, a.Hkv, (R + kRowsPerWG - 1) / kRowsPerWG);
-  hipLaunchKernelGGL(verify_partial_mfma_kernel, grid, dim3(256 * kStreams), 0, st, a, tab);
+  constexpr int kLdsBytes = kStreams * 2 * 2 * kSub * kTileBytes;
+  static_assert(kLdsBytes <= 64 * 1024, "beyond 64 KB the kernel needs the dynamic-LDS attribute");
+  const int steps = (a.chunk / kTile + kStreams * kSub - 1) / (kStreams * kSub);   // of a full split
+  if (steps <= 10)
+    hipLaunchKernelGGL(verify_partial_mfma_kernel<1>, grid, dim3(256 * kStreams), kLdsBytes, st, a, tab);
+  else
+    hipLaunchKernelGGL(verify_partial_mfma_kernel<2>, grid, dim3(256 * kStreams), kLdsBytes, st, a, tab);
+  return hipGetLastError();
+}
+
+hipError_t launch_verify_combine_mfma(const VerifyArgs &a, const SeqTable &tab, hipStream_t st) {
+  const int R = a.n_q * (a.Hq / a.Hkv);
+  const int rbs = (R + kRowsPerWG - 1) / kRowsPerWG;
+  dim3 grid(a.Hkv * rbs * 4, 4, a.B);
+  hipLaunchKernelGGL(verify_combine_tiled_kernel, grid, dim3(256), 0, st, a, tab, rbs);
   return hipGetLastError();
 }
 
