@@ -124,6 +124,18 @@ int sparrow_verify_attn(const sparrow_attn_desc *desc, const void *q, const void
                         size_t workspace_bytes, void *hip_stream);
 
 /*
+ * Profiling hook: sparrow_verify_attn with only some of its passes enqueued.  `passes` is a bit
+ * set: 1 = the split-context partial pass (reads q/k/v, writes the workspace), 2 = the combine
+ * pass (reads the workspace, writes out/lse); 3 is sparrow_verify_attn itself.  Arguments,
+ * validation and errors are those of sparrow_verify_attn; `out` is only written by pass 2 and
+ * is only meaningful if the workspace holds the partials of a matching pass 1.
+ */
+int sparrow_verify_attn_passes(const sparrow_attn_desc *desc, const void *q, const void *k,
+                               const void *v, const int32_t *cu_seqlens, const int32_t *parent,
+                               int32_t B, int32_t n_q, void *out, float *lse, void *workspace,
+                               size_t workspace_bytes, void *hip_stream, int32_t passes);
+
+/*
  * Greedy (temperature 0, lossless) acceptance: logits = hidden_rows . lm_head^T,
  * target token of every row = lowest index attaining the row maximum, then the
  * longest accepted path: starting at the last accepted token (row 0), move to

@@ -53,6 +53,8 @@ def _load() -> ctypes.CDLL:
     L.sparrow_verify_attn.restype = ctypes.c_int
     L.sparrow_verify_attn.argtypes = [dp, vp, vp, vp, i32p, vp, ctypes.c_int32, ctypes.c_int32,
                                       vp, fp, vp, ctypes.c_size_t, vp]
+    L.sparrow_verify_attn_passes.restype = ctypes.c_int
+    L.sparrow_verify_attn_passes.argtypes = L.sparrow_verify_attn.argtypes + [ctypes.c_int32]
     L.sparrow_accept_workspace.restype = ctypes.c_size_t
     L.sparrow_accept_workspace.argtypes = [ctypes.c_int32] * 5
     L.sparrow_accept.restype = ctypes.c_int
@@ -151,9 +153,10 @@ def verify_attn_workspace_bytes(q, k, v, B: int, n_q: int, total_tokens: int,
 
 
 def verify_attn(q, k, v, cu_seqlens, parent, n_q: int, scale: float = 0.0, out=None, lse=None,
-                want_lse: bool = True, workspace=None, stream=None):
-    """sparrow_verify_attn.  q [B*n_q,Hq,d]; k,v [sum(L_b+n_q),Hkv,d]; parent int32 device
-    tensor [n_q] or None (chain).  Returns (out, lse)."""
+                want_lse: bool = True, workspace=None, stream=None, passes: int = 3):
+    """sparrow_verify_attn (sparrow_verify_attn_passes when passes != 3).  q [B*n_q,Hq,d];
+    k,v [sum(L_b+n_q),Hkv,d]; parent int32 device tensor [n_q] or None (chain).
+    Returns (out, lse)."""
     cu = _host_i32(cu_seqlens)
     B = cu.shape[0] - 1
     d = _desc(q, k, v, scale)
@@ -164,10 +167,13 @@ def verify_attn(q, k, v, cu_seqlens, parent, n_q: int, scale: float = 0.0, out=N
         lse = torch.empty(q.shape[:2], dtype=torch.float32, device=q.device)
     need = int(lib.sparrow_verify_attn_workspace(ctypes.byref(d), B, n_q, int(cu[-1]))) if B > 0 else 0
     ws = _workspace(need, q.device, workspace)
-    _check(lib.sparrow_verify_attn(ctypes.byref(d), _ptr(q), _ptr(k), _ptr(v), _i32p(cu),
-                                   _ptr(parent), B, int(n_q), _ptr(out), _ptr(lse), _ptr(ws),
-                                   0 if ws is None else ws.numel() * ws.element_size(),
-                                   _stream_ptr(stream)))
+    args = (ctypes.byref(d), _ptr(q), _ptr(k), _ptr(v), _i32p(cu), _ptr(parent), B, int(n_q),
+            _ptr(out), _ptr(lse), _ptr(ws), 0 if ws is None else ws.numel() * ws.element_size(),
+            _stream_ptr(stream))
+    if passes == 3:
+        _check(lib.sparrow_verify_attn(*args))
+    else:
+        _check(lib.sparrow_verify_attn_passes(*args, int(passes)))
     return out, lse
 
 

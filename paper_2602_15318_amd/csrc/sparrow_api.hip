@@ -162,7 +162,16 @@ int sparrow_verify_attn(const sparrow_attn_desc *desc, const void *q, const void
                         const void *v, const int32_t *cu_seqlens, const int32_t *parent,
                         int32_t B, int32_t n_q, void *out, float *lse, void *workspace,
                         size_t workspace_bytes, void *hip_stream) {
+  return sparrow_verify_attn_passes(desc, q, k, v, cu_seqlens, parent, B, n_q, out, lse, workspace,
+                                    workspace_bytes, hip_stream, 3);
+}
+
+int sparrow_verify_attn_passes(const sparrow_attn_desc *desc, const void *q, const void *k,
+                               const void *v, const int32_t *cu_seqlens, const int32_t *parent,
+                               int32_t B, int32_t n_q, void *out, float *lse, void *workspace,
+                               size_t workspace_bytes, void *hip_stream, int32_t passes) {
   g_err[0] = 0;
+  if (passes < 1 || passes > 3) return fail(SPARROW_ERR_INVALID_ARG, "passes = %d (1, 2 or 3)", passes);
   if (int rc = check_desc(desc)) return rc;
   if (B < 0 || n_q < 0) return fail(SPARROW_ERR_INVALID_ARG, "B = %d, n_q = %d: negative", B, n_q);
   if (B == 0 || n_q == 0) return SPARROW_OK;
@@ -206,11 +215,15 @@ int sparrow_verify_attn(const sparrow_attn_desc *desc, const void *q, const void
   a.part_ml = (float *)((char *)workspace + bytes_o);
   a.out = out; a.lse = lse;
   hipStream_t st = (hipStream_t)hip_stream;
-  hipError_t e = mfma ? launch_verify_partial_mfma(a, tab, st)
-                      : launch_verify_partial_generic(desc->dtype, a, tab, st);
-  if (e != hipSuccess) return fail(SPARROW_ERR_DEVICE, "verify partial launch: %s", hipGetErrorString(e));
-  e = mfma ? launch_verify_combine_mfma(a, tab, st) : launch_verify_combine(desc->dtype, a, tab, st);
-  if (e != hipSuccess) return fail(SPARROW_ERR_DEVICE, "verify combine launch: %s", hipGetErrorString(e));
+  if (passes & 1) {
+    hipError_t e = mfma ? launch_verify_partial_mfma(a, tab, st)
+                        : launch_verify_partial_generic(desc->dtype, a, tab, st);
+    if (e != hipSuccess) return fail(SPARROW_ERR_DEVICE, "verify partial launch: %s", hipGetErrorString(e));
+  }
+  if (passes & 2) {
+    hipError_t e = mfma ? launch_verify_combine_mfma(a, tab, st) : launch_verify_combine(desc->dtype, a, tab, st);
+    if (e != hipSuccess) return fail(SPARROW_ERR_DEVICE, "verify combine launch: %s", hipGetErrorString(e));
+  }
   return SPARROW_OK;
 }
 

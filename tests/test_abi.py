@@ -1,0 +1,127 @@
+"""The C-ABI library: it loads, exports every symbol include/sparrow.h declares, and validates its
+host-side arguments before touching the device (CPU only: no kernel is launched here)."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "sparrow.h")
+LIB = os.path.join(ROOT, "paper_2602_15318_amd", "libsparrow.so")
+
+OK, INVALID, UNSUPPORTED, WORKSPACE = 0, -1, -2, -3
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(LIB):
+        from paper_2602_15318_amd import build
+        build.build()
+    L = ctypes.CDLL(LIB)
+    L.sparrow_last_error.restype = ctypes.c_char_p
+    L.sparrow_version.restype = ctypes.c_char_p
+    for f in ("sparrow_draft_window_attn_workspace", "sparrow_verify_attn_workspace",
+              "sparrow_accept_workspace"):
+        getattr(L, f).restype = ctypes.c_size_t
+    return L
+
+
+class Desc(ctypes.Structure):
+    _fields_ = [("dtype", ctypes.c_int32), ("n_q_heads", ctypes.c_int32),
+                ("n_kv_heads", ctypes.c_int32), ("head_dim", ctypes.c_int32),
+                ("scale", ctypes.c_float), ("kv_stride_token", ctypes.c_int64),
+                ("kv_stride_head", ctypes.c_int64)]
+
+
+def desc(dtype=1, hq=28, hkv=4, d=128, scale=0.0, st=None, sh=None):
+    return Desc(dtype, hq, hkv, d, scale, hkv * d if st is None else st, d if sh is None else sh)
+
+
+def test_every_declared_symbol_is_exported(lib):
+    text = re.sub(r"/\*.*?\*/", "", open(HEADER).read(), flags=re.S)     # declarations only
+    names = set(re.findall(r"\b(sparrow_[a-z_]+)\s*\(", text))
+    assert {"sparrow_draft_window_attn", "sparrow_verify_attn", "sparrow_accept"} <= names
+    for n in sorted(names):
+        assert hasattr(lib, n), f"{n} declared in sparrow.h but not exported"
+    assert lib.sparrow_version().decode().count(".") == 1
+
+
+P = ctypes.c_void_p(0x10000)        # fake, aligned, never dereferenced: validation fails first
+i32 = ctypes.c_int32
+
+
+def _cu(*v):
+    a = np.array(v, dtype=np.int32)
+    return a, a.ctypes.data_as(ctypes.POINTER(ctypes.c_int32))
+
+
+def test_verify_argument_validation(lib):
+    cu, cup = _cu(0, 100)
+    args = lambda d, B=1, n_q=4, ws=None, wsb=0: (ctypes.byref(d), P, P, P, cup, None, i32(B),
+                                                   i32(n_q), P, None, ws, ctypes.c_size_t(wsb), None)
+    assert lib.sparrow_verify_attn(None, P, P, P, cup, None, 1, 4, P, None, None, 0, None) == INVALID
+    assert lib.sparrow_verify_attn(*args(desc(dtype=7))) == UNSUPPORTED
+    assert lib.sparrow_verify_attn(*args(desc(d=96))) == UNSUPPORTED
+    assert lib.sparrow_verify_attn(*args(desc(hq=28, hkv=5))) == INVALID
+    assert lib.sparrow_verify_attn(*args(desc(st=100))) == INVALID          # stride < Hkv*d
+    assert lib.sparrow_verify_attn(*args(desc(scale=-1.0))) == INVALID
+    assert lib.sparrow_verify_attn(*args(desc(), n_q=65)) == UNSUPPORTED
+    assert lib.sparrow_verify_attn(*args(desc(), B=65)) == UNSUPPORTED
+    assert lib.sparrow_verify_attn(*args(desc(), n_q=101)) == UNSUPPORTED
+    cu2, cup2 = _cu(0, 3)
+    assert lib.sparrow_verify_attn(ctypes.byref(desc()), P, P, P, cup2, None, 1, 4, P, None, None, 0,
+                                   None) == INVALID                          # fewer rows than n_q
+    assert b"fewer" in lib.sparrow_last_error()
+    assert lib.sparrow_verify_attn(*args(desc())) == WORKSPACE               # NULL workspace
+    assert b"workspace" in lib.sparrow_last_error()
+    assert lib.sparrow_verify_attn(*args(desc(), ws=P, wsb=16)) == WORKSPACE
+    # misaligned q
+    assert lib.sparrow_verify_attn(ctypes.byref(desc()), ctypes.c_void_p(0x10008), P, P, cup, None, 1,
+                                   4, P, None, P, 1 << 30, None) == INVALID
+    # degenerate sizes are no-ops, also without a device
+    assert lib.sparrow_verify_attn(*args(desc(), B=0)) == OK
+    assert lib.sparrow_verify_attn(*args(desc(), n_q=0)) == OK
+    assert lib.sparrow_last_error() == b""
+    assert lib.sparrow_verify_attn_passes(*args(desc()), i32(0)) == INVALID
+
+
+def test_draft_argument_validation(lib):
+    cu, cup = _cu(0, 100)
+    ct, ctp = _cu(0, 10)
+    call = lambda d, cu_text=ctp, window=8, B=1: lib.sparrow_draft_window_attn(
+        ctypes.byref(d), P, P, P, cup, P, cu_text, i32(B), i32(window), P, None, None, 0, None)
+    assert call(desc(), window=0) == INVALID
+    assert call(desc(d=256)) == UNSUPPORTED
+    e, ep = _cu(0, 0)
+    assert call(desc(), cu_text=ep) == INVALID and b"text" in lib.sparrow_last_error()
+    big, bp = _cu(0, 101)
+    assert call(desc(), cu_text=bp) == INVALID         # more text positions than tokens
+    assert call(desc(), B=0) == OK
+    assert lib.sparrow_draft_window_attn_workspace(ctypes.byref(desc()), 1, 512) == 0
+
+
+def test_accept_argument_validation(lib):
+    call = lambda dtype=1, B=1, n_q=8, H=3584, V=152064, ws=None, wsb=0: lib.sparrow_accept(
+        i32(dtype), P, P, P, None, i32(B), i32(n_q), i32(H), i32(V), P, P, P, P, ws,
+        ctypes.c_size_t(wsb), None)
+    assert call(dtype=3) == UNSUPPORTED
+    assert call(B=8, n_q=8) == UNSUPPORTED            # 72 rows > 64
+    assert call(H=3580) == UNSUPPORTED                # rows not multiples of 16 bytes
+    assert call(V=0) == INVALID
+    assert call() == WORKSPACE
+    assert call(B=0) == OK
+
+
+def test_workspace_queries(lib):
+    d = desc()
+    v = lib.sparrow_verify_attn_workspace(ctypes.byref(d), 1, 8, ctypes.c_int64(26120))
+    # about one split per compute unit: 64 splits x 4 KV heads x 32.5 KB
+    assert 7 * 2 ** 20 < v < 10 * 2 ** 20
+    assert lib.sparrow_verify_attn_workspace(ctypes.byref(d), 0, 8, ctypes.c_int64(26120)) == 0
+    f32 = desc(dtype=0, hq=4, hkv=1, d=64)
+    assert lib.sparrow_verify_attn_workspace(ctypes.byref(f32), 1, 4, ctypes.c_int64(516)) > 0
+    a = lib.sparrow_accept_workspace(1, 1, 8, 3584, 152064)
+    assert 0 < a < 2 ** 20
+    assert lib.sparrow_accept_workspace(0, 1, 4, 256, 1024) > 0
