@@ -75,6 +75,36 @@ __device__ __forceinline__ float wave_sum(float v) {
   return v;
 }
 
+// Cross-lane helpers on the vector ALU (DPP and the gfx950 row-swap instructions) instead of
+// ds_bpermute, which goes through the LDS crossbar.
+template <int kCtrl> __device__ __forceinline__ float dpp_f32(float v) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), kCtrl, 0xF, 0xF, true));
+}
+// Sum over aligned groups of N consecutive lanes (N = 8, 16 or 32); every lane gets the result.
+template <int N> __device__ __forceinline__ float group_sum(float v) {
+  static_assert(N == 8 || N == 16 || N == 32, "lane group size");
+  v += dpp_f32<0xB1>(v);          // quad_perm [1,0,3,2]
+  v += dpp_f32<0x4E>(v);          // quad_perm [2,3,0,1]
+  v += dpp_f32<0x141>(v);         // row_half_mirror: lanes i <-> 7-i of each 8
+  if (N >= 16) v += dpp_f32<0x140>(v);   // row_mirror: lanes i <-> 15-i of each 16
+  if (N >= 32) {
+    auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    v = __uint_as_float(r[0]) + __uint_as_float(r[1]);
+  }
+  return v;
+}
+// Value of lane (lane ^ O) for O = 8, 16 or 32.
+template <int O> __device__ __forceinline__ float lane_xor(float v, int lane) {
+  static_assert(O == 8 || O == 16 || O == 32, "supported distances");
+  if (O == 8) return dpp_f32<0x128>(v);              // row_ror 8 within each row of 16
+  if (O == 16) {
+    auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    return __uint_as_float((lane & 16) ? r[0] : r[1]);
+  }
+  auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+  return __uint_as_float((lane & 32) ? r[0] : r[1]);
+}
+
 // Ancestor-or-self bit set of draft row i: bit j set <=> row i may attend draft row j.
 // parent == nullptr means a chain.  Requires parent[a] < a (then the walk ends) and i < 64.
 __device__ __forceinline__ unsigned long long ancestor_mask(const int32_t *parent, int i) {

@@ -8,6 +8,8 @@
 // lane group keeps its own online-softmax stream (m, l, o), streams are merged once at the end
 // (lane groups by shuffles, wavefronts through LDS).  Up to 8 gathered tokens per lane group are
 // in flight at a time.
+#include <type_traits>
+
 #include "common.hpp"
 #include "draft_window_attn.hpp"
 
@@ -91,8 +93,7 @@ draft_window_attn_kernel(DraftArgs a, DraftTable tab) {
         float s = 0.f;
 #pragma unroll
         for (int e = 0; e < PER; ++e) s = fmaf(qf[r][e], kf[e], s);
-#pragma unroll
-        for (int o = LPT / 2; o >= 1; o >>= 1) s += __shfl_xor(s, o, 64);
+        s = group_sum<LPT>(s);
         s = valid ? s : -INFINITY;
         const float m_new = fmaxf(m[r], s);
         const float alpha = fast_exp2(m[r] - m_new);
@@ -106,23 +107,26 @@ draft_window_attn_kernel(DraftArgs a, DraftTable tab) {
   }
 
   // merge the TPW lane-group streams of this wavefront
-#pragma unroll
-  for (int o = LPT; o < 64; o <<= 1) {
+  auto merge_with = [&](auto xor_tag) {
+    constexpr int O = decltype(xor_tag)::value;
 #pragma unroll
     for (int r = 0; r < kDraftRows; ++r) {
-      const float m_o = __shfl_xor(m[r], o, 64);
-      const float l_o = __shfl_xor(l[r], o, 64);
+      const float m_o = lane_xor<O>(m[r], lane);
+      const float l_o = lane_xor<O>(l[r], lane);
       const float m_new = fmaxf(m[r], m_o);
       const float wa = fast_exp2(m[r] - m_new), wb = fast_exp2(m_o - m_new);
       l[r] = l[r] * wa + l_o * wb;
       m[r] = m_new;
 #pragma unroll
       for (int e = 0; e < PER; ++e) {
-        const float a_o = __shfl_xor(acc[r][e], o, 64);
+        const float a_o = lane_xor<O>(acc[r][e], lane);
         acc[r][e] = acc[r][e] * wa + a_o * wb;
       }
     }
-  }
+  };
+  if (LPT <= 8) merge_with(std::integral_constant<int, 8>{});
+  if (LPT <= 16) merge_with(std::integral_constant<int, 16>{});
+  merge_with(std::integral_constant<int, 32>{});
   if (sub == 0) {
 #pragma unroll
     for (int r = 0; r < kDraftRows; ++r) {
