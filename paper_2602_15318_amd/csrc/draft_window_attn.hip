@@ -3,7 +3,8 @@
 // text-position index, so keys and values at visual positions are never addressed.
 //
 // The whole job is at most a few hundred KB, so it is latency-bound: a single launch, one
-// workgroup of 16 wavefronts per (sequence, KV head, block of up to 2 query heads of the group).
+// workgroup of 16 wavefronts per (sequence, query head): the job is too small to be bandwidth-bound, so the work is
+// spread over as many compute units as there are heads and each re-reads its KV head's window from L2.
 // A group of LPT lanes owns one token (each lane one 16-byte slice of the K and V rows); every
 // lane group keeps its own online-softmax stream (m, l, o), streams are merged once at the end
 // (lane groups by shuffles, wavefronts through LDS).  Up to 8 gathered tokens per lane group are
@@ -16,7 +17,7 @@
 namespace sparrow {
 
 constexpr int kDraftWaves = 16;
-constexpr int kDraftRows = 2;     // query heads per workgroup
+constexpr int kDraftRows = 1;     // query heads per workgroup
 constexpr int kDraftUnroll = 8;   // tokens in flight per lane group
 
 template <typename T, int D>
@@ -44,20 +45,18 @@ draft_window_attn_kernel(DraftArgs a, DraftTable tab) {
   const T *K = (const T *)a.k + c * a.stride_head + vec * PER;
   const T *V = (const T *)a.v + c * a.stride_head + vec * PER;
 
-  // this lane's slice of the (pre-scaled) queries
+  // this lane's slice of the queries (raw storage words; the scale is applied to the scores)
+  constexpr bool kBf16 = std::is_same<T, bf16_t>::value;
+  u32x4 qw[kDraftRows];
   float qf[kDraftRows][PER];
 #pragma unroll
   for (int r = 0; r < kDraftRows; ++r) {
+    qw[r] = (u32x4){0u, 0u, 0u, 0u};
     if (r < nr) {
       const int h = c * g + r0 + r;
-      u32x4 qw = *(const u32x4 *)((const T *)a.q + ((int64_t)b * a.Hq + h) * D + vec * PER);
-      Elem<T>::unpack(qw, qf[r]);
-#pragma unroll
-      for (int u = 0; u < PER; ++u) qf[r][u] *= a.scale_log2;
-    } else {
-#pragma unroll
-      for (int u = 0; u < PER; ++u) qf[r][u] = 0.f;
+      qw[r] = *(const u32x4 *)((const T *)a.q + ((int64_t)b * a.Hq + h) * D + vec * PER);
     }
+    Elem<T>::unpack(qw[r], qf[r]);
   }
 
   float m[kDraftRows], l[kDraftRows], acc[kDraftRows][PER];
@@ -86,14 +85,24 @@ draft_window_attn_kernel(DraftArgs a, DraftTable tab) {
     for (int u = 0; u < kDraftUnroll; ++u) {
       const bool valid = (j0 + u * STEP) < n;
       float kf[PER], vf[PER];
-      Elem<T>::unpack(kw[u], kf);
+      if (!kBf16) Elem<T>::unpack(kw[u], kf);
       Elem<T>::unpack(vw[u], vf);
 #pragma unroll
       for (int r = 0; r < kDraftRows; ++r) {
         float s = 0.f;
+        if (kBf16) {   // packed bf16 dot products with fp32 accumulation, no unpacking of K
+          typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+          const unsigned qe[4] = {qw[r].x, qw[r].y, qw[r].z, qw[r].w};
+          const unsigned ke[4] = {kw[u].x, kw[u].y, kw[u].z, kw[u].w};
 #pragma unroll
-        for (int e = 0; e < PER; ++e) s = fmaf(qf[r][e], kf[e], s);
-        s = group_sum<LPT>(s);
+          for (int e = 0; e < 4; ++e)
+            s = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, qe[e]),
+                                                __builtin_bit_cast(bf16x2, ke[e]), s, false);
+        } else {
+#pragma unroll
+          for (int e = 0; e < PER; ++e) s = fmaf(qf[r][e], kf[e], s);
+        }
+        s = group_sum<LPT>(s) * a.scale_log2;
         s = valid ? s : -INFINITY;
         const float m_new = fmaxf(m[r], s);
         const float alpha = fast_exp2(m[r] - m_new);
