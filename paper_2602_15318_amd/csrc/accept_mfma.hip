@@ -13,7 +13,8 @@
 //   - logits never leave the registers: every lane keeps the best (value, lowest index) of the
 //     vocabulary rows it has seen for its column; one candidate per (wavefront, row) is written at
 //     the end and reduced by the finalize kernel.
-// More than 16 rows (trees, batches) are handled as several row blocks, each a full pass over W.
+// More than 16 rows (trees, batches): the k-split kernel takes 32 rows per pass over W, the
+// fallback kernel 16.
 #include "accept.hpp"
 #include "common.hpp"
 
@@ -134,11 +135,14 @@ lm_head_mfma_kernel(AcceptArgs a, int row0) {
 // group are summed through LDS; wavefront g < 4 then owns the argmax bookkeeping of tile g.
 constexpr int kKsGroup = 4;               // vocabulary tiles (of 16 rows) per group
 
-template <int NW>
+// NB = blocks of 16 hidden rows handled in one pass over W (1 or 2); the vocabulary group is
+// kKsGroup / NB tiles so that the partial logits held in registers stay at 16 per lane.
+template <int NW, int NB>
 __global__ void __launch_bounds__(NW * 64)
 lm_head_ksplit_kernel(AcceptArgs a, int row0) {
+  constexpr int G = kKsGroup / NB;          // vocabulary tiles per group
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  // [NW][16 KB] staging, then [NW][kKsGroup][64] f32x4 partial logits
+  // [NW][16 KB] staging, then [NW][G][64] f32x4 partial logits
   const int tid = threadIdx.x, lane = tid & 63;
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int n = lane & 15, c4 = lane >> 4;
@@ -147,14 +151,14 @@ lm_head_ksplit_kernel(AcceptArgs a, int row0) {
   unsigned char *stg = smem + w * 16384;
   f32x4 *red = reinterpret_cast<f32x4 *>(smem + NW * 16384);
 
-  const int n_groups = (V + 16 * kKsGroup - 1) / (16 * kKsGroup);
+  const int n_groups = (V + 16 * G - 1) / (16 * G);
   const int my_groups = n_groups > (int)blockIdx.x ? (n_groups - blockIdx.x + gridDim.x - 1) / gridDim.x : 0;
-  const int n_tiles = my_groups * kKsGroup;          // tiles this wavefront streams
+  const int n_tiles = my_groups * G;          // tiles this wavefront streams
 
   // tile t of this workgroup -> first vocabulary row
   auto tile_row0 = [&](int t) {
-    const int grp = blockIdx.x + (t / kKsGroup) * gridDim.x;
-    return (grp * kKsGroup + (t % kKsGroup)) * 16;
+    const int grp = blockIdx.x + (t / G) * gridDim.x;
+    return (grp * G + (t % G)) * 16;
   };
   // 16 loads of 1 KB: load r = the k-slice of row r of the tile (rows clamped to the last row).
   // Issued unconditionally (tile index clamped) so that the number of loads in flight is static.
@@ -169,90 +173,122 @@ lm_head_ksplit_kernel(AcceptArgs a, int row0) {
   };
   issue(0);
 
-  // B operands: lane (n, c4) holds hidden[row0 + n][512 w + 32 ks + 8 c4 .. +8], ks = 0..15
-  bf16x8 hreg[16];
-  {
-    const bool ok = row0 + n < a.M;
-    const bf16_t *hp = (const bf16_t *)a.hidden + (int64_t)(ok ? row0 + n : 0) * H + 512 * w + 8 * c4;
+  // B operands: lane (n, c4) holds hidden[row0 + 16 nb + n][512 w + 32 ks + 8 c4 .. +8], ks = 0..15
+  bf16x8 hreg[NB][16];
+#pragma unroll
+  for (int nb = 0; nb < NB; ++nb) {
+    const int row = row0 + 16 * nb + n;
+    const bool ok = row < a.M;
+    const bf16_t *hp = (const bf16_t *)a.hidden + (int64_t)(ok ? row : 0) * H + 512 * w + 8 * c4;
 #pragma unroll
     for (int ks = 0; ks < 16; ++ks) {
       u32x4 v = *(const u32x4 *)(hp + 32 * ks);
       if (!ok) v = (u32x4){0u, 0u, 0u, 0u};
-      hreg[ks] = __builtin_bit_cast(bf16x8, v);
+      hreg[nb][ks] = __builtin_bit_cast(bf16x8, v);
     }
   }
 
   // staging: lane i of load r holds chunk i (16 bytes) of row r; stored at chunk position
   // (i & ~15) | ((i & 15) ^ r) so that the A-operand reads (16 rows, same chunk) hit all banks
   const int a_base = n * 1024;      // A read: row n, chunk 4 ks + c4
-  float best = -INFINITY;
-  int best_i = 0x7fffffff;
-  f32x4 part[kKsGroup];
+  float best[NB];
+  int best_i[NB];
+#pragma unroll
+  for (int nb = 0; nb < NB; ++nb) { best[nb] = -INFINITY; best_i[nb] = 0x7fffffff; }
+  f32x4 part[G][NB];
 
   for (int t = 0; t < n_tiles; ++t) {
 #pragma unroll
     for (int r = 0; r < 16; ++r)
       *reinterpret_cast<u32x4 *>(stg + r * 1024 + (((lane & ~15) | ((lane & 15) ^ r)) << 4)) = buf[r];
     issue(t + 1);
-    f32x4 acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
+    f32x4 acc[NB][2];
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) {
+      acc[nb][0] = (f32x4){0.f, 0.f, 0.f, 0.f};
+      acc[nb][1] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    }
 #pragma unroll
     for (int ks = 0; ks < 16; ks += 2) {
       const int ch0 = 4 * ks + c4, ch1 = ch0 + 4;
       const bf16x8 a0 = *reinterpret_cast<const bf16x8 *>(stg + a_base + (((ch0 & ~15) | ((ch0 & 15) ^ n)) << 4));
       const bf16x8 a1 = *reinterpret_cast<const bf16x8 *>(stg + a_base + (((ch1 & ~15) | ((ch1 & 15) ^ n)) << 4));
-      acc0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0, hreg[ks], acc0, 0, 0, 0);
-      acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, hreg[ks + 1], acc1, 0, 0, 0);
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb) {
+        acc[nb][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0, hreg[nb][ks], acc[nb][0], 0, 0, 0);
+        acc[nb][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, hreg[nb][ks + 1], acc[nb][1], 0, 0, 0);
+      }
     }
-    const int g = t % kKsGroup;
+    const int g = t % G;
     // static register index for part[]
 #pragma unroll
-    for (int gg = 0; gg < kKsGroup; ++gg)
-      if (gg == g) part[gg] = acc0 + acc1;
-    if (g == kKsGroup - 1) {
-      // sum the group's partial logits over the wavefronts
-      f32x4 *rb = red;
+    for (int gg = 0; gg < G; ++gg)
+      if (gg == g) {
 #pragma unroll
-      for (int gg = 0; gg < kKsGroup; ++gg) rb[(w * kKsGroup + gg) * 64 + lane] = part[gg];
-      __syncthreads();
-      if (w < kKsGroup) {
-        f32x4 sum = rb[(0 * kKsGroup + w) * 64 + lane];
-#pragma unroll
-        for (int ww = 1; ww < NW; ++ww) sum += rb[(ww * kKsGroup + w) * 64 + lane];
-        const int vbase = tile_row0(t - (kKsGroup - 1) + w) + 4 * c4;
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-          if (vbase + i < V && sum[i] > best) { best = sum[i]; best_i = vbase + i; }
+        for (int nb = 0; nb < NB; ++nb) part[gg][nb] = acc[nb][0] + acc[nb][1];
       }
-      __syncthreads();   // reads done before the next group's partials are written
+    if (g == G - 1) {
+      // sum the group's partial logits over the wavefronts, one block of hidden rows at a time
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb) {
+#pragma unroll
+        for (int gg = 0; gg < G; ++gg) red[(w * G + gg) * 64 + lane] = part[gg][nb];
+        __syncthreads();
+        if (w < G) {
+          f32x4 sum = red[(0 * G + w) * 64 + lane];
+#pragma unroll
+          for (int ww = 1; ww < NW; ++ww) sum += red[(ww * G + w) * 64 + lane];
+          const int vbase = tile_row0(t - (G - 1) + w) + 4 * c4;
+#pragma unroll
+          for (int i = 0; i < 4; ++i)
+            if (vbase + i < V && sum[i] > best[nb]) { best[nb] = sum[i]; best_i[nb] = vbase + i; }
+        }
+        __syncthreads();   // reads done before the next partials are written
+      }
     }
   }
 
-  // candidates: wavefronts 0..3 hold, per lane, the best of tiles g = w over all groups
+  // candidates: wavefronts 0..G-1 hold, per lane, the best of tiles g = w over all groups; the
+  // workgroup always fills kKsGroup candidate slots (the others stay at -inf)
   if (w < kKsGroup) {
 #pragma unroll
-    for (int o = 16; o <= 32; o <<= 1) {
-      const float ov = __shfl_xor(best, o, 64);
-      const int oi = __shfl_xor(best_i, o, 64);
-      if (ov > best || (ov == best && oi < best_i)) { best = ov; best_i = oi; }
-    }
-    if (c4 == 0 && row0 + n < a.M) {
-      const int slot = blockIdx.x * kKsGroup + w;
-      a.cand_val[(int64_t)(row0 + n) * a.n_cand + slot] = best;
-      a.cand_idx[(int64_t)(row0 + n) * a.n_cand + slot] = best_i;
+    for (int nb = 0; nb < NB; ++nb) {
+      float bv = best[nb];
+      int bi = best_i[nb];
+#pragma unroll
+      for (int o = 16; o <= 32; o <<= 1) {
+        const float ov = __shfl_xor(bv, o, 64);
+        const int oi = __shfl_xor(bi, o, 64);
+        if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
+      }
+      const int row = row0 + 16 * nb + n;
+      if (c4 == 0 && row < a.M) {
+        const int slot = blockIdx.x * kKsGroup + w;
+        a.cand_val[(int64_t)row * a.n_cand + slot] = bv;
+        a.cand_idx[(int64_t)row * a.n_cand + slot] = bi;
+      }
     }
   }
 }
 
-template <int NW>
-hipError_t launch_ksplit(const AcceptArgs &a, hipStream_t st) {
+template <int NW, int NB>
+hipError_t launch_ksplit_nb(const AcceptArgs &a, int row0, hipStream_t st) {
   const int lds = NW * 16384 + NW * kKsGroup * 64 * 16;
   static const hipError_t attr = hipFuncSetAttribute(
-      (const void *)lm_head_ksplit_kernel<NW>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+      (const void *)lm_head_ksplit_kernel<NW, NB>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
   if (attr != hipSuccess) return attr;
-  for (int row0 = 0; row0 < a.M; row0 += 16) {
-    hipLaunchKernelGGL((lm_head_ksplit_kernel<NW>), dim3(kLmBlocks), dim3(NW * 64), lds, st, a, row0);
-    hipError_t e = hipGetLastError();
+  hipLaunchKernelGGL((lm_head_ksplit_kernel<NW, NB>), dim3(kLmBlocks), dim3(NW * 64), lds, st, a, row0);
+  return hipGetLastError();
+}
+
+// One pass over W per 32 hidden rows (16 for the last odd block).
+template <int NW>
+hipError_t launch_ksplit(const AcceptArgs &a, hipStream_t st) {
+  for (int row0 = 0; row0 < a.M;) {
+    const bool two = a.M - row0 > 16;
+    const hipError_t e = two ? launch_ksplit_nb<NW, 2>(a, row0, st) : launch_ksplit_nb<NW, 1>(a, row0, st);
     if (e != hipSuccess) return e;
+    row0 += two ? 32 : 16;
   }
   return hipSuccess;
 }
