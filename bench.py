@@ -165,7 +165,10 @@ def main() -> int:
         for l in range(cfg.n_layers):
             verify_layer(l)
     us_verify_step = time_graph(capture(verify_all), max(5, args.steps // 2))
-    us_draft = time_graph(capture(draft), 200)
+    def draft_many():                      # 28 calls back to back: per-call time without the
+        for _ in range(28):                # replay launch latency of a one-kernel graph
+            draft()
+    us_draft = time_graph(capture(draft_many), 20) / 28
     us_accept = time_graph(capture(accept), 20)
 
     # dominant kernel: the split-context partial pass of verify attention (one launch per layer).

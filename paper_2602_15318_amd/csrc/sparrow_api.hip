@@ -188,13 +188,41 @@ int sparrow_verify_attn_passes(const sparrow_attn_desc *desc, const void *q, con
                   b, cu_seqlens[b + 1] - cu_seqlens[b], n_q);
   const int64_t total = cu_seqlens[B];   // the figure the workspace query is given
   const bool mfma = use_mfma_verify(desc);
-  const int chunk = plan_chunk(desc, n_q, total, mfma);
+  // Splits per sequence in proportion to its length (at least one), within the budget of about one
+  // workgroup per compute unit that plan_chunk aims at; each sequence is then cut into equal
+  // pieces, so that every workgroup of the call streams about the same number of bytes.
+  const int chunk0 = plan_chunk(desc, n_q, total, mfma);
+  const int slot_budget = (int)((total + chunk0 - 1) / chunk0);
   SeqTable tab;
   memset(&tab, 0, sizeof(tab));
   for (int b = 0; b <= B; ++b) tab.cu_len[b] = cu_seqlens[b];
-  for (int b = 0; b < B; ++b) {
-    const int len = cu_seqlens[b + 1] - cu_seqlens[b];
-    tab.cu_split[b + 1] = tab.cu_split[b] + (len + chunk - 1) / chunk;
+  int chunk = 0;
+  {
+    int ns[SPARROW_MAX_BATCH];
+    int used = 0;
+    for (int b = 0; b < B; ++b) {
+      const int len = cu_seqlens[b + 1] - cu_seqlens[b];
+      ns[b] = (int)((int64_t)len * slot_budget / (total > 0 ? total : 1));
+      if (ns[b] < 1) ns[b] = 1;
+      used += ns[b];
+    }
+    // hand the slots lost to rounding down to the sequences with the longest pieces
+    while (used < slot_budget) {
+      int worst = 0;
+      double worst_len = -1.0;
+      for (int b = 0; b < B; ++b) {
+        const double piece = (double)(cu_seqlens[b + 1] - cu_seqlens[b]) / ns[b];
+        if (piece > worst_len) { worst_len = piece; worst = b; }
+      }
+      ++ns[worst];
+      ++used;
+    }
+    for (int b = 0; b < B; ++b) {
+      const int len = cu_seqlens[b + 1] - cu_seqlens[b];
+      tab.cu_split[b + 1] = tab.cu_split[b] + ns[b];
+      const int piece = split_len(len, ns[b]);
+      if (piece > chunk) chunk = piece;
+    }
   }
   const int n_slots = tab.cu_split[B];
   const size_t need = verify_ws_bytes(desc, n_slots, n_q);

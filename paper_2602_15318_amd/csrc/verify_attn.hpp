@@ -19,7 +19,8 @@ struct VerifyArgs {
   const void *q, *k, *v;
   const int32_t *parent;  // device, or nullptr for a chain
   int32_t B, n_q, Hq, Hkv, d;
-  int32_t chunk;          // tokens per split
+  int32_t chunk;          // longest split of the call, in tokens (the kernels derive each
+                          // sequence's own split length from SeqTable)
   int32_t n_slots;        // cu_split[B]
   float scale_log2;       // softmax scale * log2(e)
   int64_t stride_tok, stride_head;
@@ -30,6 +31,13 @@ struct VerifyArgs {
   void *out;              // [B*n_q, Hq, d]
   float *lse;             // [B*n_q, Hq] or nullptr
 };
+
+// Token range [t0, t1) of a split: a sequence of `len` rows with `ns` splits is cut into pieces of
+// ceil(len / ns) rounded up to a whole 32-token tile (the last piece takes what is left, possibly
+// nothing), so that all workgroups of a sequence stream the same number of bytes.
+__host__ __device__ __forceinline__ int split_len(int len, int ns) {
+  return ((len + ns - 1) / ns + 31) / 32 * 32;
+}
 
 // Which sequence owns split slot `slot` (linear scan; B <= SPARROW_MAX_BATCH).
 __device__ __forceinline__ int seq_of_slot(const SeqTable &tab, int B, int slot) {

@@ -82,8 +82,9 @@ verify_partial_mfma_kernel(VerifyArgs a, SeqTable tab) {
   const int b = seq_of_slot(tab, a.B, slot);
   const int len = tab.cu_len[b + 1] - tab.cu_len[b];
   const int L = len - a.n_q;
-  const int t0 = (slot - tab.cu_split[b]) * a.chunk;
-  const int t1 = min(len, t0 + a.chunk);
+  const int piece = split_len(len, tab.cu_split[b + 1] - tab.cu_split[b]);
+  const int t0 = min(len, (slot - tab.cu_split[b]) * piece);
+  const int t1 = min(len, t0 + piece);
   const int n_tiles = (t1 - t0 + kTile - 1) / kTile;                    // of the workgroup
   const int n_steps = (n_tiles + kStreams * kSub - 1) / (kStreams * kSub);   // loop trips
   const int64_t tok_base = tab.cu_len[b];
