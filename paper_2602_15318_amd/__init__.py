@@ -4,10 +4,16 @@ Thin Python binding over the C-ABI library built from csrc/ (see include/sparrow
 draft_window_attn, verify_attn and accept.  All computation runs in the HIP kernels;
 PyTorch only provides device memory and streams.
 """
-from .binding import (SparrowError, accept, accept_workspace_bytes, draft_window_attn,
-                      last_error, library_path, verify_attn, verify_attn_workspace_bytes,
-                      version, AttnDesc, lib)
-
 __all__ = ["SparrowError", "accept", "accept_workspace_bytes", "draft_window_attn", "last_error",
            "library_path", "verify_attn", "verify_attn_workspace_bytes", "version", "AttnDesc",
            "lib"]
+
+
+def __getattr__(name):
+    # The binding (and with it libsparrow.so) is loaded on first use of any public name, so that
+    # `paper_2602_15318_amd.build` stays importable on a tree that has not been built yet.  A
+    # missing library raises ImportError there: there is no fallback path.
+    if name in __all__:
+        from . import binding
+        return getattr(binding, name)
+    raise AttributeError(f"module {__name__!r} has no attribute {name!r}")

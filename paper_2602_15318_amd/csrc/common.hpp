@@ -121,4 +121,22 @@ __device__ __forceinline__ unsigned long long ancestor_mask(const int32_t *paren
   return m;
 }
 
+// Same bit set, computed by a whole wavefront at once: lane j keeps parent[j] in a register and
+// every lane walks its own row's path with cross-lane reads, so the walk costs one global load
+// instead of one per tree level.  Must be called by all 64 lanes (i may differ per lane);
+// n_q <= 64.
+__device__ __forceinline__ unsigned long long ancestor_mask_wave(const int32_t *parent, int n_q,
+                                                                 int i, int lane) {
+  if (parent == nullptr) return (2ull << i) - 1ull;
+  const int pv = lane < n_q ? parent[lane] : -1;
+  unsigned long long m = 0;
+  int a = i;
+  for (int steps = 0; steps < n_q && __builtin_amdgcn_ballot_w64(a >= 0) != 0ull; ++steps) {
+    if (a >= 0) m |= 1ull << a;
+    const int p = __shfl(pv, a >= 0 ? a : 0, 64);
+    a = (a >= 0 && p < a) ? p : -1;
+  }
+  return m;
+}
+
 }  // namespace sparrow

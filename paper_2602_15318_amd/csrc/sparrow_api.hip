@@ -29,6 +29,7 @@ int fail(int code, const char *fmt, ...) {
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 constexpr int kNumCU = 256;   // MI355X
+constexpr int kNumXCD = 8;    // 32 compute units and one L2 each
 
 int check_desc(const sparrow_attn_desc *d) {
   if (!d) return fail(SPARROW_ERR_INVALID_ARG, "desc is NULL");
@@ -60,9 +61,16 @@ float scale_log2_of(const sparrow_attn_desc *d) {
 // pure overhead traffic, so no more splits than it takes to occupy the chip.
 int plan_chunk(const sparrow_attn_desc *d, int32_t n_q, int64_t total_tokens, bool mfma) {
   const int R = n_q * (d->n_q_heads / d->n_kv_heads);
-  const int rows_per_wg = mfma ? 64 : 16;
-  const int rbs = (R + rows_per_wg - 1) / rows_per_wg;
-  int slots = kNumCU / (d->n_kv_heads * rbs);
+  const int rbs = mfma ? verify_mfma_row_blocks(R) : (R + 15) / 16;
+  int slots;
+  if (mfma) {
+    // The row blocks of one (split, KV head) run side by side on one XCD (they share the K/V
+    // stream through its L2), one workgroup per compute unit: whole groups per XCD only.
+    const int groups_per_xcd = (kNumCU / kNumXCD) / rbs > 0 ? (kNumCU / kNumXCD) / rbs : 1;
+    slots = groups_per_xcd * kNumXCD / d->n_kv_heads;
+  } else {
+    slots = kNumCU / (d->n_kv_heads * rbs);
+  }
   if (slots < 1) slots = 1;
   int64_t chunk = (total_tokens + slots - 1) / slots;
   chunk = (int64_t)round_up((size_t)chunk, 32);
@@ -70,8 +78,12 @@ int plan_chunk(const sparrow_attn_desc *d, int32_t n_q, int64_t total_tokens, bo
   return (int)chunk;
 }
 
-bool use_mfma_verify(const sparrow_attn_desc *d) {
-  return verify_partial_mfma_supported(d->dtype, d->head_dim);
+// The matrix-core kernel addresses a sequence's K/V rows by 32-bit byte offsets; judged on the
+// call's total token count so that the workspace query and the call always agree.
+bool use_mfma_verify(const sparrow_attn_desc *d, int64_t total_tokens) {
+  return verify_partial_mfma_supported(d->dtype, d->head_dim) &&
+         d->kv_stride_token < (1ll << 24) &&
+         total_tokens * d->kv_stride_token * 2 < (1ll << 31);
 }
 
 // Workspace split: partial outputs first, then (max, sum) pairs, each rounded up to 256 bytes.
@@ -89,9 +101,9 @@ void verify_ws_layout(const sparrow_attn_desc *d, int64_t slots, int32_t n_q, bo
   }
 }
 
-size_t verify_ws_bytes(const sparrow_attn_desc *d, int64_t max_slots, int32_t n_q) {
+size_t verify_ws_bytes(const sparrow_attn_desc *d, int64_t max_slots, int32_t n_q, bool mfma) {
   size_t bo, bml;
-  verify_ws_layout(d, max_slots, n_q, use_mfma_verify(d), &bo, &bml);
+  verify_ws_layout(d, max_slots, n_q, mfma, &bo, &bml);
   return bo + bml;
 }
 }  // namespace
@@ -153,9 +165,10 @@ int sparrow_draft_window_attn(const sparrow_attn_desc *desc, const void *q, cons
 size_t sparrow_verify_attn_workspace(const sparrow_attn_desc *desc, int32_t B, int32_t n_q,
                                      int64_t total_tokens) {
   if (check_desc(desc) != SPARROW_OK || B <= 0 || n_q <= 0 || total_tokens <= 0) return 0;
-  const int chunk = plan_chunk(desc, n_q, total_tokens, use_mfma_verify(desc));
+  const bool mfma = use_mfma_verify(desc, total_tokens);
+  const int chunk = plan_chunk(desc, n_q, total_tokens, mfma);
   const int64_t max_slots = (total_tokens + chunk - 1) / chunk + B;
-  return verify_ws_bytes(desc, max_slots, n_q);
+  return verify_ws_bytes(desc, max_slots, n_q, mfma);
 }
 
 int sparrow_verify_attn(const sparrow_attn_desc *desc, const void *q, const void *k,
@@ -187,7 +200,7 @@ int sparrow_verify_attn_passes(const sparrow_attn_desc *desc, const void *q, con
       return fail(SPARROW_ERR_INVALID_ARG, "sequence %d has %d rows, fewer than its n_q = %d draft rows",
                   b, cu_seqlens[b + 1] - cu_seqlens[b], n_q);
   const int64_t total = cu_seqlens[B];   // the figure the workspace query is given
-  const bool mfma = use_mfma_verify(desc);
+  const bool mfma = use_mfma_verify(desc, total);
   // Splits per sequence in proportion to its length (at least one), within the budget of about one
   // workgroup per compute unit that plan_chunk aims at; each sequence is then cut into equal
   // pieces, so that every workgroup of the call streams about the same number of bytes.
@@ -225,7 +238,7 @@ int sparrow_verify_attn_passes(const sparrow_attn_desc *desc, const void *q, con
     }
   }
   const int n_slots = tab.cu_split[B];
-  const size_t need = verify_ws_bytes(desc, n_slots, n_q);
+  const size_t need = verify_ws_bytes(desc, n_slots, n_q, mfma);
   if (!workspace || workspace_bytes < need)
     return fail(SPARROW_ERR_WORKSPACE, "workspace of %zu bytes needed, %zu given%s", need,
                 workspace_bytes, workspace ? "" : " (NULL)");

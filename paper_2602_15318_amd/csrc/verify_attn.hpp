@@ -52,6 +52,8 @@ hipError_t launch_verify_partial_generic(int dtype, const VerifyArgs &a, const S
 // Partial pass, matrix-core version: bf16, head_dim 128.
 bool verify_partial_mfma_supported(int dtype, int head_dim);
 hipError_t launch_verify_partial_mfma(const VerifyArgs &a, const SeqTable &tab, hipStream_t st);
+// Workgroups per (split, KV head) for R = n_q * (Hq / Hkv) rows.
+int verify_mfma_row_blocks(int R);
 // Its partials use a tiled layout of their own: workspace floats per (split, KV head, block of 64
 // rows) unit, and the matching combine pass.
 int64_t verify_mfma_unit_floats_o();

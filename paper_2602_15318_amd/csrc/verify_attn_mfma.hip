@@ -17,6 +17,8 @@
 //   O^T += V^T P^T  B = P^T straight from the score registers (k index = the lane's own eight
 //                 tokens), A = V^T through the transposing LDS read ds_read_b64_tr_b16.
 // The online-softmax state (m, l) and the rescale factor are per lane (= per query row).
+#include <type_traits>
+
 #include "common.hpp"
 #include "verify_attn.hpp"
 
@@ -30,6 +32,7 @@ constexpr int kTileBytes = kTile * kRowBytes;
 constexpr int kSub = 1;                   // 32-token tiles per stream per step
 constexpr int kRowsPerWG = 64;
 constexpr int kStreams = 2;
+constexpr float kSlack = 8.0f;            // log2 units a score may exceed a row's reference point
 
 // Swizzle of the 16-byte chunk index by the token row: a bijection on 0..15 per row whose upper
 // three bits differ for rows 0..7, so a half-wavefront of transposing reads (8 rows x 32 bytes)
@@ -59,13 +62,16 @@ __device__ __forceinline__ float quad_sum(float v) {
   return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
 
+// kQT = 16-row tiles per wavefront: 1 serves up to 64 rows per workgroup (chains), 2 serves 128
+// (draft trees): the K and V^T operands read from LDS then feed two row tiles each, and a tree of
+// R rows needs half as many passes over the K/V stream.
 // kPrefetch = steps in flight in registers.  The whole split of a workgroup is only a handful of
 // steps at decode-time sizes (7 at 26k context on 256 compute units), so a deep look-ahead turns
 // the kernel into "load most of it, then compute": depth 1 is fastest there, depth 2 once the
 // splits get long (batches, very long contexts).
-template <int kPrefetch>
+template <int kPrefetch, int kQT>
 __global__ void __launch_bounds__(256 * kStreams)
-verify_partial_mfma_kernel(VerifyArgs a, SeqTable tab) {
+verify_partial_mfma_kernel(VerifyArgs a, SeqTable tab, int rbs) {
   // [stream][buf][K,V][kSub tiles]; after the main loop the first 34 KB are reused for the merge
   extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
   constexpr int kStepBytes = kSub * kTileBytes;            // K (or V) rows of one stream step
@@ -73,12 +79,25 @@ verify_partial_mfma_kernel(VerifyArgs a, SeqTable tab) {
     return lds + ((strm_ * 2 + buf) * 2 + kv) * kStepBytes;
   };
 
-  const int tid = threadIdx.x & 255, strm = threadIdx.x >> 8;
-  const int w = tid >> 6, lane = tid & 63;
+  // wavefront-uniform indices as scalars, so that everything derived from them (which rows are
+  // live, whether a step touches the split end) is decided by scalar branches
+  const int wave_id = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int strm = wave_id >> 2, w = wave_id & 3;
+  const int tid = threadIdx.x & 255, lane = threadIdx.x & 63;
   const int n = lane & 15, c4 = lane >> 4;
-  const int slot = blockIdx.x, c = blockIdx.y, rb = blockIdx.z;
+  // Workgroup -> (split, KV head, row block).  Workgroups are handed to the 8 XCDs round-robin by
+  // their linear index, and the row blocks of one (split, KV head) stream the same K/V: they get
+  // indices that are equal modulo 8 and adjacent in that XCD's order, so they run at the same time
+  // on one XCD and all but the first fetch of a tile hit its L2.  (Only the speed depends on the
+  // round-robin placement.)
+  const int xj = blockIdx.x >> 3;
+  const int rb = xj % rbs;
+  const int grp = (xj / rbs) * 8 + (blockIdx.x & 7);       // split + n_slots * KV head
+  if (grp >= a.n_slots * a.Hkv) return;                    // padding of the last round of 8
+  const int slot = grp % a.n_slots, c = grp / a.n_slots;
   const int g = a.Hq / a.Hkv;
   const int R = a.n_q * g;
+  const int rbs64 = (R + kRowsPerWG - 1) / kRowsPerWG;     // 64-row units of the partial layout
   const int b = seq_of_slot(tab, a.B, slot);
   const int len = tab.cu_len[b + 1] - tab.cu_len[b];
   const int L = len - a.n_q;
@@ -87,16 +106,25 @@ verify_partial_mfma_kernel(VerifyArgs a, SeqTable tab) {
   const int t1 = min(len, t0 + piece);
   const int n_tiles = (t1 - t0 + kTile - 1) / kTile;                    // of the workgroup
   const int n_steps = (n_tiles + kStreams * kSub - 1) / (kStreams * kSub);   // loop trips
-  const int64_t tok_base = tab.cu_len[b];
-  const bf16_t *Kg = (const bf16_t *)a.k + c * a.stride_head;
-  const bf16_t *Vg = (const bf16_t *)a.v + c * a.stride_head;
+  // K/V of this sequence and head; a token row is addressed by a 32-bit byte offset from here
+  // (the host checks that a sequence's K/V spans less than 2 GB)
+  const int64_t seq_off = (int64_t)tab.cu_len[b] * a.stride_tok + (int64_t)c * a.stride_head;
+  const unsigned char *Kg = (const unsigned char *)((const bf16_t *)a.k + seq_off);
+  const unsigned char *Vg = (const unsigned char *)((const bf16_t *)a.v + seq_off);
+  const unsigned int row_bytes = (unsigned int)a.stride_tok * 2u;
 
-  // ---- this lane's query row
-  const int rho = rb * kRowsPerWG + 16 * w + n;
-  const bool row_ok = rho < R;
-  const bool wave_active = (rb * kRowsPerWG + 16 * w) < R;
-  const int i_row = row_ok ? rho / g : 0;
-  const int h = row_ok ? c * g + rho % g : 0;
+  // ---- this lane's query rows: one per row tile
+  bool row_ok[kQT];
+  int i_row[kQT], h[kQT];
+  int n_act = 0;                                  // row tiles of this wavefront that hold rows
+#pragma unroll
+  for (int qt = 0; qt < kQT; ++qt) {
+    const int rho = (rb * kQT + qt) * kRowsPerWG + 16 * w + n;
+    row_ok[qt] = rho < R;
+    if ((rb * kQT + qt) * kRowsPerWG + 16 * w < R) n_act = qt + 1;
+    i_row[qt] = row_ok[qt] ? rho / g : 0;
+    h[qt] = row_ok[qt] ? c * g + rho % g : 0;
+  }
 
   // ---- loader: in step `st` stream `strm` owns tiles (st*kStreams + strm)*kSub .. +kSub, i.e.
   // 32*kSub consecutive tokens; thread -> rows tid/16 + 16 j, 16-byte chunk tid%16.  Rows past
@@ -110,7 +138,7 @@ verify_partial_mfma_kernel(VerifyArgs a, SeqTable tab) {
 #pragma unroll
     for (int j = 0; j < kLd; ++j) {
       const int r = min(tb + ld_row + 16 * j, t1 - 1);
-      const int64_t o = (tok_base + r) * a.stride_tok + ld_ch * 8;
+      const unsigned int o = (unsigned int)r * row_bytes + (unsigned int)ld_ch * 16u;
       sg[j] = __builtin_nontemporal_load((const u32x4 *)(Kg + o));
       sg[kLd + j] = __builtin_nontemporal_load((const u32x4 *)(Vg + o));
     }
@@ -128,14 +156,18 @@ verify_partial_mfma_kernel(VerifyArgs a, SeqTable tab) {
 
   // ---- first step, then Q^T (B operand of the score MFMA: lane (n, c4) holds
   // Q[row][32*ks + 8*c4 .. +8]), then the rest of the look-ahead.
-  bf16x8 qreg[4];
+  bf16x8 qreg[kQT][4];
   {
     issue(0, stage[0]);
-    const int64_t qrow = row_ok ? ((int64_t)b * a.n_q + i_row) * a.Hq + h : 0;   // clamped, zeroed below
-    const bf16_t *qp = (const bf16_t *)a.q + qrow * 128 + 8 * c4;
-    u32x4 qv[4];
+    u32x4 qv[kQT][4];
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks) qv[ks] = *(const u32x4 *)(qp + 32 * ks);
+    for (int qt = 0; qt < kQT; ++qt) {
+      // rows past R read row 0 (in bounds) and are zeroed below
+      const int64_t qrow = row_ok[qt] ? ((int64_t)b * a.n_q + i_row[qt]) * a.Hq + h[qt] : 0;
+      const bf16_t *qp = (const bf16_t *)a.q + qrow * 128 + 8 * c4;
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks) qv[qt][ks] = *(const u32x4 *)(qp + 32 * ks);
+    }
     // The memory pipeline of a compute unit serves requests in issue order and a wavefront
     // issues all its loads back to back: without this barrier the look-ahead of the wavefronts
     // that issue first would queue ahead of the FIRST step of the others (measured: 3 us of
@@ -149,14 +181,23 @@ verify_partial_mfma_kernel(VerifyArgs a, SeqTable tab) {
     static_assert(kAfterQ < 64, "vmcnt is a 6-bit counter");
     __builtin_amdgcn_s_waitcnt(0x0F70 | (kAfterQ & 15) | ((kAfterQ >> 4) << 14));
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks) {
-      if (!row_ok) qv[ks] = (u32x4){0u, 0u, 0u, 0u};
-      qreg[ks] = __builtin_bit_cast(bf16x8, qv[ks]);
+    for (int qt = 0; qt < kQT; ++qt)
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks) {
+        if (!row_ok[qt]) qv[qt][ks] = (u32x4){0u, 0u, 0u, 0u};
+        qreg[qt][ks] = __builtin_bit_cast(bf16x8, qv[qt][ks]);
+      }
+  }
+  // draft rows a row may attend (bit j <=> draft row j); only needed if the split reaches them
+  unsigned long long anc[kQT];
+#pragma unroll
+  for (int qt = 0; qt < kQT; ++qt) {
+    anc[qt] = 0ull;
+    if (t1 > L) {                                            // uniform over the workgroup
+      anc[qt] = ancestor_mask_wave(a.parent, a.n_q, i_row[qt], lane);
+      if (!row_ok[qt]) anc[qt] = 0ull;
     }
   }
-  // draft rows this row may attend (bit j <=> draft row j); only needed if the split reaches them
-  unsigned long long anc = 0ull;
-  if (row_ok && t1 > L) anc = ancestor_mask(a.parent, i_row);
 
   // LDS read offsets
   const int k_off = n * kRowBytes;                 // + 16-row slab, chunk (4*ks + c4) ^ swz(n)
@@ -167,76 +208,122 @@ verify_partial_mfma_kernel(VerifyArgs a, SeqTable tab) {
   const int v_off = v_row * kRowBytes + ((s16 & 1) << 3);   // + chunk (2*mt + ((s16>>1)&1)) ^ swz
   const int v_chb = (s16 >> 1) & 1;
 
-  float m_run = kNegBig, l_run = 0.f;
-  f32x4 o_acc[8];
+  float m_run[kQT];
+  f32x4 l_acc[kQT];       // running sum of a row's exponentials, the same value in all 4 entries
+  f32x4 o_acc[kQT][8];
+  constexpr bool kMfmaRowSum = true;
+  bf16x8 ones;
 #pragma unroll
-  for (int mt = 0; mt < 8; ++mt) o_acc[mt] = (f32x4){0.f, 0.f, 0.f, 0.f};
+  for (int e = 0; e < 8; ++e) ones[e] = (__bf16)1.0f;
+#pragma unroll
+  for (int qt = 0; qt < kQT; ++qt) {
+    m_run[qt] = kNegBig;
+    l_acc[qt] = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int mt = 0; mt < 8; ++mt) o_acc[qt][mt] = (f32x4){0.f, 0.f, 0.f, 0.f};
+  }
 
   // One step of one stream: 32*kSub tokens against the wavefront's 16 rows, one joint softmax
   // update (a single running-max / rescale for the whole step).
-  auto compute = [&](int st, int buf) {
+  auto compute = [&](int st, int buf, auto na_tag) {
+    constexpr int NA = decltype(na_tag)::value;   // live row tiles (the leading ones)
     const unsigned char *Ks = lds_at(strm, buf, 0);
     const unsigned char *Vs = lds_at(strm, buf, 1);
     const int tb = t0 + (st * kStreams + strm) * kSub * kTile;
-    f32x4 s[kLd];
+    f32x4 s[NA][kLd];
 #pragma unroll
     for (int j = 0; j < kLd; ++j) {
       bf16x8 ka[4];
 #pragma unroll
       for (int ks = 0; ks < 4; ++ks)
         ka[ks] = lds_read_b128(Ks + j * 16 * kRowBytes + k_off + (((4 * ks + c4) ^ k_swz) << 4));
-      s[j] = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int qt = 0; qt < NA; ++qt) s[qt][j] = (f32x4){0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int ks = 0; ks < 4; ++ks)
-        s[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[ks], qreg[ks], s[j], 0, 0, 0);
+#pragma unroll
+        for (int qt = 0; qt < NA; ++qt)
+          s[qt][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[ks], qreg[qt][ks], s[qt][j], 0, 0, 0);
     }
-    // scale, mask, online softmax (per lane = per query row)
-    float sc[4 * kLd];
+    // mask, online softmax (per lane = per query row).  Scores stay unscaled until the exponent:
+    // exp2(s * scale_log2 - m) is one fused multiply-add per score (scale_log2 > 0, so the
+    // maximum can be taken before scaling).
+    const bool edge = tb + kSub * kTile > min(t1, L);   // uniform: split end or draft rows in reach
+    if (kQT > 1) __builtin_amdgcn_sched_barrier(0);     // keep the V^T reads below the softmax
+    bf16x8 pb[NA][kSub];
 #pragma unroll
-    for (int j = 0; j < kLd; ++j)
-#pragma unroll
-      for (int i = 0; i < 4; ++i) sc[4 * j + i] = s[j][i] * a.scale_log2;
-    if (tb + kSub * kTile > min(t1, L)) {   // wavefront-uniform: step touches the split end or draft rows
+    for (int qt = 0; qt < NA; ++qt) {
+      float sc[4 * kLd];
 #pragma unroll
       for (int j = 0; j < kLd; ++j)
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          const int tok = tb + 16 * j + 4 * c4 + i;
-          const int dj = tok - L;
-          const bool vis = (dj < 0) | (((anc >> (dj & 63)) & 1ull) != 0ull);
-          sc[4 * j + i] = ((tok < t1) & vis) ? sc[4 * j + i] : -INFINITY;
-        }
-    }
-    float mx = sc[0];
+        for (int i = 0; i < 4; ++i) sc[4 * j + i] = s[qt][j][i];
+      if (edge) {
 #pragma unroll
-    for (int e = 1; e < 4 * kLd; ++e) mx = fmaxf(mx, sc[e]);
-    mx = quad_max(mx);
-    const float m_new = fmaxf(m_run, mx);
-    const float alpha = fast_exp2(m_run - m_new);
-    m_run = m_new;
-    float psum = 0.f;
-    bf16x8 pb[kSub];
+        for (int j = 0; j < kLd; ++j)
 #pragma unroll
-    for (int u = 0; u < kSub; ++u)
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        const float p = fast_exp2(sc[8 * u + e] - m_new);
-        psum += p;
-        pb[u][e] = (__bf16)p;
+          for (int i = 0; i < 4; ++i) {
+            const int tok = tb + 16 * j + 4 * c4 + i;
+            const int dj = tok - L;
+            const bool vis = (dj < 0) | (((anc[qt] >> (dj & 63)) & 1ull) != 0ull);
+            sc[4 * j + i] = ((tok < t1) & vis) ? sc[4 * j + i] : -INFINITY;
+          }
       }
-    l_run = l_run * alpha + psum;
+      float mx = sc[0];
+#pragma unroll
+      for (int e = 1; e < 4 * kLd; ++e) mx = fmaxf(mx, sc[e]);
+      mx *= a.scale_log2;
+      // The reference point m of a row moves only when some score of the wavefront's tile lies
+      // more than kSlack above it (exponentials then stay below 2^kSlack, far from overflow, and
+      // softmax does not depend on the reference point): the cross-lane maximum, the rescale
+      // factor and the 32 accumulator multiplies are skipped for almost every tile.
+      if (__builtin_amdgcn_ballot_w64(mx > m_run[qt] + kSlack) != 0ull) {
+        const float m_new = fmaxf(m_run[qt], quad_max(mx));
+        const float alpha = fast_exp2(m_run[qt] - m_new);
+        m_run[qt] = m_new;
+        if (kMfmaRowSum) l_acc[qt] *= alpha; else l_acc[qt][0] *= alpha;
+#pragma unroll
+        for (int mt = 0; mt < 8; ++mt) o_acc[qt][mt] *= alpha;
+      }
+#pragma unroll
+      for (int u = 0; u < kSub; ++u) {
+        float psum = 0.f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const float p = fast_exp2(fmaf(sc[8 * u + e], a.scale_log2, -m_run[qt]));
+          if (!kMfmaRowSum) psum += p;
+          pb[qt][u][e] = (__bf16)p;
+        }
+        // row sums on the matrix cores: every row of ones . P^T is the sum over the 32 tokens
+        // (with two row tiles the registers do not allow it: per-lane sums, merged at the end)
+        if (kMfmaRowSum)
+          l_acc[qt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, pb[qt][u], l_acc[qt], 0, 0, 0);
+        else
+          l_acc[qt][0] += psum;
+      }
+    }
+    if (kQT > 1) __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int mt = 0; mt < 8; ++mt) {
-      o_acc[mt] *= alpha;
       const int ch = ((2 * mt + v_chb) ^ v_swz) << 4;
+      if (kQT > 1 && mt == 4) __builtin_amdgcn_sched_barrier(0);    // at most 4 d-tiles of V^T in flight
 #pragma unroll
       for (int u = 0; u < kSub; ++u) {
         const bf16x4 va = lds_read_tr(Vs + (2 * u) * 16 * kRowBytes + v_off + ch);
         const bf16x4 vb = lds_read_tr(Vs + (2 * u + 1) * 16 * kRowBytes + v_off + ch);
         const bf16x8 vt = __builtin_shufflevector(va, vb, 0, 1, 2, 3, 4, 5, 6, 7);
-        o_acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vt, pb[u], o_acc[mt], 0, 0, 0);
+#pragma unroll
+        for (int qt = 0; qt < NA; ++qt)
+          o_acc[qt][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vt, pb[qt][u], o_acc[qt][mt], 0, 0, 0);
       }
     }
+  };
+
+  // A wavefront with a partly filled pair of row tiles computes both (the empty one on a zero
+  // query): a second, one-tile instance of the step in the same kernel costs more registers than
+  // the kernel has.
+  auto run = [&](int st, int buf) {
+    if (n_act > 0) compute(st, buf, std::integral_constant<int, kQT>{});
   };
 
   // ---- main loop, unrolled by the prefetch depth so that the staging registers are static.
@@ -250,7 +337,7 @@ verify_partial_mfma_kernel(VerifyArgs a, SeqTable tab) {
       stash(buf, stage[p]);
       issue(st + kPrefetch, stage[p]);
       __syncthreads();
-      if ((st * kStreams + strm) * kSub < n_tiles && wave_active) compute(st, buf);
+      if ((st * kStreams + strm) * kSub < n_tiles) run(st, buf);
     }
   }
   // remainder (n_steps % kPrefetch trips): everything it needs is already in flight
@@ -261,39 +348,43 @@ verify_partial_mfma_kernel(VerifyArgs a, SeqTable tab) {
       const int buf = st & 1;
       stash(buf, stage[p]);
       __syncthreads();
-      if ((st * kStreams + strm) * kSub < n_tiles && wave_active) compute(st, buf);
+      if ((st * kStreams + strm) * kSub < n_tiles) run(st, buf);
     }
   }
 
   // ---- merge the two streams (stream 1 -> LDS -> stream 0) and write the split's partials in
   // register layout: [slot][kv head][row block][wavefront][mt][lane] x 4 floats, so that every
   // store instruction writes 1 KB of contiguous memory.
-  l_run = quad_sum(l_run);
-  __syncthreads();                      // all tile reads done: LDS is free
   f32x4 *mo = reinterpret_cast<f32x4 *>(lds);                                  // [w][mt][lane]
   float *mm = reinterpret_cast<float *>(lds + 4 * 8 * 64 * 16);                // [w][lane][m,l]
-  if (strm == 1) {
 #pragma unroll
-    for (int mt = 0; mt < 8; ++mt) mo[(w * 8 + mt) * 64 + lane] = o_acc[mt];
-    mm[(w * 64 + lane) * 2] = m_run;
-    mm[(w * 64 + lane) * 2 + 1] = l_run;
-  }
-  __syncthreads();
-  if (strm == 0 && wave_active) {
-    const float m1 = mm[(w * 64 + lane) * 2], l1 = mm[(w * 64 + lane) * 2 + 1];
-    const float m_new = fmaxf(m_run, m1);
-    const float a0 = fast_exp2(m_run - m_new), a1 = fast_exp2(m1 - m_new);
-    const int64_t unit = ((int64_t)slot * a.Hkv + c) * gridDim.z + rb;       // (split, head, row block)
-    f32x4 *po = reinterpret_cast<f32x4 *>(a.part_o) + (unit * 4 + w) * (8 * 64) + lane;
+  for (int qt = 0; qt < kQT; ++qt) {
+    const float l_mine = kMfmaRowSum ? l_acc[qt][0] : quad_sum(l_acc[qt][0]);
+    __syncthreads();                    // all tile reads (and the previous merge) done: LDS is free
+    if (strm == 1) {
 #pragma unroll
-    for (int mt = 0; mt < 8; ++mt) {
-      const f32x4 o1 = mo[(w * 8 + mt) * 64 + lane];
-      po[mt * 64] = o_acc[mt] * a0 + o1 * a1;
+      for (int mt = 0; mt < 8; ++mt) mo[(w * 8 + mt) * 64 + lane] = o_acc[qt][mt];
+      mm[(w * 64 + lane) * 2] = m_run[qt];
+      mm[(w * 64 + lane) * 2 + 1] = l_mine;
     }
-    if (c4 == 0) {
-      float *pml = a.part_ml + (unit * kRowsPerWG + 16 * w + n) * 2;
-      pml[0] = m_new;
-      pml[1] = l_run * a0 + l1 * a1;
+    __syncthreads();
+    if (strm == 0 && qt < n_act) {
+      const float m1 = mm[(w * 64 + lane) * 2], l1 = mm[(w * 64 + lane) * 2 + 1];
+      const float m_new = fmaxf(m_run[qt], m1);
+      const float a0 = fast_exp2(m_run[qt] - m_new), a1 = fast_exp2(m1 - m_new);
+      // unit = (split, KV head, block of 64 rows)
+      const int64_t unit = ((int64_t)slot * a.Hkv + c) * rbs64 + rb * kQT + qt;
+      f32x4 *po = reinterpret_cast<f32x4 *>(a.part_o) + (unit * 4 + w) * (8 * 64) + lane;
+#pragma unroll
+      for (int mt = 0; mt < 8; ++mt) {
+        const f32x4 o1 = mo[(w * 8 + mt) * 64 + lane];
+        po[mt * 64] = o_acc[qt][mt] * a0 + o1 * a1;
+      }
+      if (c4 == 0) {
+        float *pml = a.part_ml + (unit * kRowsPerWG + 16 * w + n) * 2;
+        pml[0] = m_new;
+        pml[1] = l_mine * a0 + l1 * a1;
+      }
     }
   }
 }
@@ -382,16 +473,24 @@ bool verify_partial_mfma_supported(int dtype, int head_dim) {
 int64_t verify_mfma_unit_floats_o() { return 4 * 8 * 64 * 4; }
 int64_t verify_mfma_unit_floats_ml() { return kRowsPerWG * 2; }
 
+// Row blocks per (split, KV head): workgroups of 64 rows for R <= 64, of 128 rows beyond.
+int verify_mfma_row_blocks(int R) { return R <= kRowsPerWG ? 1 : (R + 2 * kRowsPerWG - 1) / (2 * kRowsPerWG); }
+
 hipError_t launch_verify_partial_mfma(const VerifyArgs &a, const SeqTable &tab, hipStream_t st) {
   const int R = a.n_q * (a.Hq / a.Hkv);
-  dim3 grid(a.n_slots, a.Hkv, (R + kRowsPerWG - 1) / kRowsPerWG);
+  const int rbs = verify_mfma_row_blocks(R);
+  dim3 grid((a.n_slots * a.Hkv + 7) / 8 * 8 * rbs), block(256 * kStreams);
   constexpr int kLdsBytes = kStreams * 2 * 2 * kSub * kTileBytes;
   static_assert(kLdsBytes <= 64 * 1024, "beyond 64 KB the kernel needs the dynamic-LDS attribute");
   const int steps = (a.chunk / kTile + kStreams * kSub - 1) / (kStreams * kSub);   // of a full split
-  if (steps <= 10)
-    hipLaunchKernelGGL(verify_partial_mfma_kernel<1>, grid, dim3(256 * kStreams), kLdsBytes, st, a, tab);
+  if (R > kRowsPerWG && steps <= 10)
+    hipLaunchKernelGGL((verify_partial_mfma_kernel<1, 2>), grid, block, kLdsBytes, st, a, tab, rbs);
+  else if (R > kRowsPerWG)
+    hipLaunchKernelGGL((verify_partial_mfma_kernel<2, 2>), grid, block, kLdsBytes, st, a, tab, rbs);
+  else if (steps <= 10)
+    hipLaunchKernelGGL((verify_partial_mfma_kernel<1, 1>), grid, block, kLdsBytes, st, a, tab, rbs);
   else
-    hipLaunchKernelGGL(verify_partial_mfma_kernel<2>, grid, dim3(256 * kStreams), kLdsBytes, st, a, tab);
+    hipLaunchKernelGGL((verify_partial_mfma_kernel<2, 1>), grid, block, kLdsBytes, st, a, tab, rbs);
   return hipGetLastError();
 }
 
