@@ -46,6 +46,9 @@ def _load():
         _lib.oracle_accept.restype = ctypes.c_int
         _lib.oracle_logits.restype = None
         _lib.oracle_argmax.restype = None
+        _lib.oracle_hsr_fc.restype = None
+        _lib.oracle_draft_qkv.restype = None
+        _lib.oracle_rope_table.restype = None
     return _lib
 
 
@@ -165,3 +168,56 @@ def accept_step(hidden, lm_head, draft_ids, parent, B: int, n_q: int):
     alen, path, bonus = accept(ids, draft_ids, parent, B, n_q)
     return {"target_ids": ids, "margin": margin, "accept_len": alen,
             "accept_path": path, "bonus_id": bonus}
+
+
+def hsr_fc(embed, token_ids, h_prev, w_fc, b_fc=None) -> np.ndarray:
+    """z = FC(e (+) h) (Eq. 1): embed [vocab, H] (only the rows of token_ids are widened),
+    h_prev [M, H], w_fc [H, 2H], b_fc [H] or None.  Returns z [M, H] float64."""
+    lib = _load()
+    tok = _i32(token_ids)
+    e = _f64(np.asarray(embed)[tok])
+    h = _f64(h_prev)
+    M, H = h.shape
+    W = _f64(w_fc)
+    assert e.shape == (M, H) and W.shape == (H, 2 * H)
+    b = None if b_fc is None else _f64(b_fc)
+    z = np.empty((M, H), dtype=np.float64)
+    lib.oracle_hsr_fc(_ptr(e, _dp), _ptr(h, _dp), _ptr(W, _dp), _ptr(b, _dp), ctypes.c_int(M),
+                      ctypes.c_int(H), _ptr(z, _dp))
+    return z
+
+
+def draft_qkv(z, gamma, eps: float, w_qkv, b_qkv, rope_cos, rope_sin, n_q_heads: int,
+              n_kv_heads: int, head_dim: int):
+    """RMSNorm -> QKV projection (+ bias) -> rotary embedding of q and k.
+    Returns q [M, Hq, d], k [M, Hkv, d], v [M, Hkv, d] float64."""
+    lib = _load()
+    z = _f64(z)
+    M, H = z.shape
+    N = (n_q_heads + 2 * n_kv_heads) * head_dim
+    W = _f64(w_qkv)
+    assert W.shape == (N, H)
+    g = _f64(gamma)
+    b = None if b_qkv is None else _f64(b_qkv)
+    cs, sn = _f64(rope_cos), _f64(rope_sin)
+    assert cs.shape == (M, head_dim // 2) and sn.shape == cs.shape
+    q = np.empty((M, n_q_heads, head_dim), dtype=np.float64)
+    k = np.empty((M, n_kv_heads, head_dim), dtype=np.float64)
+    v = np.empty((M, n_kv_heads, head_dim), dtype=np.float64)
+    lib.oracle_draft_qkv(_ptr(z, _dp), _ptr(g, _dp), ctypes.c_double(eps), _ptr(W, _dp),
+                         _ptr(b, _dp), _ptr(cs, _dp), _ptr(sn, _dp), ctypes.c_int(M),
+                         ctypes.c_int(H), ctypes.c_int(n_q_heads), ctypes.c_int(n_kv_heads),
+                         ctypes.c_int(head_dim), _ptr(q, _dp), _ptr(k, _dp), _ptr(v, _dp))
+    return q, k, v
+
+
+def rope_table(positions, head_dim: int, theta: float = 1.0e6):
+    """(cos, sin) [M, d/2] float64 of the rotate-half rotary embedding."""
+    lib = _load()
+    pos = _i32(positions)
+    M = pos.shape[0]
+    cs = np.empty((M, head_dim // 2), dtype=np.float64)
+    sn = np.empty_like(cs)
+    lib.oracle_rope_table(_ptr(pos, _ip), ctypes.c_int(M), ctypes.c_int(head_dim),
+                          ctypes.c_double(theta), _ptr(cs, _dp), _ptr(sn, _dp))
+    return cs, sn

@@ -18,7 +18,10 @@
  * closed forms (constant V, zero K, one dominant key), invariants (all-text
  * window == causal decode, n_q = 1 == decode, chain-shaped tree == chain,
  * per-path decomposition of a tree, row permutation, GQA == replicated MHA),
- * and brute-force enumeration of small acceptance problems.
+ * and brute-force enumeration of small acceptance problems; for the draft's
+ * input side (tests/test_oracle_hsr.py) numpy matmul on the concatenated
+ * input, the Qwen2 RMSNorm / rotary-embedding modules of the transformers
+ * package run in float64, and the rotation invariants of the rotary embedding.
  * Nothing numeric is printed in the paper for these steps, so no golden value
  * from the paper exists; end-to-end accepted-length tables are out of reach
  * (trained weights and videos are not available).
@@ -206,4 +209,100 @@ int oracle_accept(const int32_t *target_ids, const int32_t *draft_ids, const int
         bonus_id[b] = t[cur + 1];
     }
     return 0;
+}
+
+/* ------------------------------------------------------------------------
+ * Draft input side (the step before the draft's window attention).
+ * ------------------------------------------------------------------------ */
+
+/* Hidden state reuse (Section "Visually-Aware Text-Anchored Window Attention
+ * via Hidden State Reuse", Eq. 1): z_t = FC(e_t (+) h_{t-1}), the projection
+ * of the concatenation of the current token's embedding and the target
+ * model's hidden state of the previous step back to the model width.
+ *   e [M, H] (embedding rows already gathered), h [M, H],
+ *   W [H, 2H] row-major (output feature n reads W[n, 0:H] . e + W[n, H:2H] . h),
+ *   bias [H] or NULL, z [M, H]. */
+void oracle_hsr_fc(const double *e, const double *h, const double *W, const double *bias,
+                   int M, int H, double *z)
+{
+    #pragma omp parallel for schedule(static)
+    for (int n = 0; n < H; ++n) {
+        const double *w = W + (int64_t)n * 2 * H;
+        for (int m = 0; m < M; ++m) {
+            double acc = bias ? bias[n] : 0.0;
+            for (int x = 0; x < H; ++x) acc += w[x] * e[(int64_t)m * H + x];
+            for (int x = 0; x < H; ++x) acc += w[H + x] * h[(int64_t)m * H + x];
+            z[(int64_t)m * H + n] = acc;
+        }
+    }
+}
+
+/* Input side of the draft's decoder layer, with the target's layer
+ * architecture (the paper builds the draft from the target's layer type and
+ * gives no formula of its own; this is the RMSNorm / biased QKV projection /
+ * rotate-half rotary embedding of the Qwen2 family):
+ *   u = z / sqrt(mean(z^2) + eps) * gamma
+ *   y = W u + bias,            W [(Hq + 2 Hkv) d, H], rows ordered q heads, k heads, v heads
+ *   rotary embedding on every q and k head with the row's (cos, sin) [d/2]:
+ *     out[i]       = x[i] cos[i] - x[i + d/2] sin[i]
+ *     out[i + d/2] = x[i + d/2] cos[i] + x[i] sin[i]          (i < d/2)
+ * Outputs q [M, Hq, d], k [M, Hkv, d] (rotated), v [M, Hkv, d]. */
+void oracle_draft_qkv(const double *z, const double *gamma, double eps, const double *W,
+                      const double *bias, const double *rope_cos, const double *rope_sin,
+                      int M, int H, int Hq, int Hkv, int d, double *q, double *k, double *v)
+{
+    const int N = (Hq + 2 * Hkv) * d;
+    const int half = d / 2;
+    double *u = (double *)malloc(sizeof(double) * (size_t)M * H);
+    double *y = (double *)malloc(sizeof(double) * (size_t)M * N);
+    for (int m = 0; m < M; ++m) {
+        double ss = 0.0;
+        for (int x = 0; x < H; ++x) ss += z[(int64_t)m * H + x] * z[(int64_t)m * H + x];
+        const double r = 1.0 / sqrt(ss / H + eps);
+        for (int x = 0; x < H; ++x) u[(int64_t)m * H + x] = z[(int64_t)m * H + x] * r * gamma[x];
+    }
+    #pragma omp parallel for schedule(static)
+    for (int n = 0; n < N; ++n) {
+        const double *w = W + (int64_t)n * H;
+        for (int m = 0; m < M; ++m) {
+            double acc = bias ? bias[n] : 0.0;
+            for (int x = 0; x < H; ++x) acc += w[x] * u[(int64_t)m * H + x];
+            y[(int64_t)m * N + n] = acc;
+        }
+    }
+    for (int m = 0; m < M; ++m) {
+        const double *cs = rope_cos + (int64_t)m * half, *sn = rope_sin + (int64_t)m * half;
+        for (int hd = 0; hd < Hq + 2 * Hkv; ++hd) {
+            const double *x = y + (int64_t)m * N + (int64_t)hd * d;
+            double *o;
+            int rotate = 1;
+            if (hd < Hq) o = q + ((int64_t)m * Hq + hd) * d;
+            else if (hd < Hq + Hkv) o = k + ((int64_t)m * Hkv + (hd - Hq)) * d;
+            else { o = v + ((int64_t)m * Hkv + (hd - Hq - Hkv)) * d; rotate = 0; }
+            for (int i = 0; i < half; ++i) {
+                if (rotate) {
+                    o[i] = x[i] * cs[i] - x[i + half] * sn[i];
+                    o[i + half] = x[i + half] * cs[i] + x[i] * sn[i];
+                } else {
+                    o[i] = x[i];
+                    o[i + half] = x[i + half];
+                }
+            }
+        }
+    }
+    free(u);
+    free(y);
+}
+
+/* Rotary tables of the rotate-half convention: angle(pos, i) = pos * theta^(-2 i / d), i < d/2. */
+void oracle_rope_table(const int32_t *pos, int M, int d, double theta, double *rope_cos,
+                       double *rope_sin)
+{
+    const int half = d / 2;
+    for (int m = 0; m < M; ++m)
+        for (int i = 0; i < half; ++i) {
+            const double ang = (double)pos[m] * pow(theta, -2.0 * i / d);
+            rope_cos[(int64_t)m * half + i] = cos(ang);
+            rope_sin[(int64_t)m * half + i] = sin(ang);
+        }
 }

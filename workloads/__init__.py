@@ -5,7 +5,8 @@ This module only *draws inputs*: Gaussian tensors, position-type layouts
 token ids.  It contains none of the method's arithmetic (no attention, no
 softmax, no GEMM, no argmax, no acceptance) and is imported by the tests and
 the benchmark to feed the very same bits to the CPU oracle and to the HIP
-library.  Neither of those two imports the other.
+library (the rotary cos/sin rows of the draft's input side are drawn here too:
+both sides receive them as inputs).  Neither of those two imports the other.
 
 Shapes follow the five workload configurations C1..C5 (a tiny fp32 case, a
 Qwen2.5-VL-7B-shaped single layer at 8k context, a 26k-context long-video
@@ -360,3 +361,61 @@ def accept_case(cfg: Config, seed: int = 0, vocab: Optional[int] = None,
         hidden = _normal(rng, (rows, cfg.hidden), cfg.dtype)
     draft_ids = rng.integers(0, V, size=B * n_q).astype(np.int32)
     return AcceptCase(cfg, hidden, W, draft_ids, parent, n_q, planted_ids)
+
+
+@dataclass
+class HsrCase:
+    """Inputs of the draft's input side for M new tokens (one per sequence in a
+    chain draft): the embedding table and token ids, the target's hidden state
+    of the previous step, the FC projection of the concatenation (Eq. 1), and
+    the draft layer's input norm, QKV projection and rotary rows."""
+    cfg: Config
+    embed: np.ndarray        # [V, H]
+    token_ids: np.ndarray    # int32 [M]
+    h_prev: np.ndarray       # [M, H]
+    w_fc: np.ndarray         # [H, 2H]
+    b_fc: np.ndarray         # [H]
+    norm_weight: np.ndarray  # [H]
+    eps: float
+    w_qkv: np.ndarray        # [(Hq + 2 Hkv) d, H]
+    b_qkv: np.ndarray        # [(Hq + 2 Hkv) d]
+    positions: np.ndarray    # int32 [M], sequence-local position of every new token
+    rope_cos: np.ndarray     # float32 [M, d/2]
+    rope_sin: np.ndarray     # float32 [M, d/2]
+
+
+def rope_rows(positions: np.ndarray, head_dim: int, theta: float = 1.0e6):
+    """float32 (cos, sin) [M, d/2] rows of a rotary table, angle = pos * theta^(-2i/d); the
+    caller of the library owns this table (one per forward pass, shared by all layers)."""
+    i = np.arange(head_dim // 2, dtype=np.float64)
+    ang = np.asarray(positions, dtype=np.float64)[:, None] * theta ** (-2.0 * i / head_dim)[None, :]
+    return np.cos(ang).astype(np.float32), np.sin(ang).astype(np.float32)
+
+
+def hsr_case(cfg: Config, seed: int = 0, rows: Optional[int] = None,
+             embed: Optional[np.ndarray] = None, vocab: Optional[int] = None,
+             positions: Optional[np.ndarray] = None) -> HsrCase:
+    """Weights ~ N(0, 0.02) (initialiser range), biases N(0, 0.02) / N(0, 0.5) (QKV biases of
+    the Qwen2 family are of order 1), norm weight 1 + N(0, 0.1), hidden state N(0, 1).  `embed`
+    may be any [V, H] table (the benchmark passes the lm_head matrix it already holds)."""
+    M = cfg.batch if rows is None else rows
+    H, d = cfg.hidden, cfg.head_dim
+    N = (cfg.n_q_heads + 2 * cfg.n_kv_heads) * d
+    rng = _rng(seed, 701)
+    if embed is None:
+        embed = lm_head_weights(cfg, seed + 7919, vocab)
+    V = embed.shape[0]
+    token_ids = rng.integers(0, V, size=M).astype(np.int32)
+    h_prev = _normal(rng, (M, H), cfg.dtype)
+    w_fc = _normal(rng, (H, 2 * H), cfg.dtype, 0.02)
+    b_fc = _normal(rng, (H,), cfg.dtype, 0.02)
+    norm_weight = to_storage(1.0 + 0.1 * rng.standard_normal(size=H, dtype=np.float32), cfg.dtype)
+    w_qkv = _normal(rng, (N, H), cfg.dtype, 0.02)
+    b_qkv = _normal(rng, (N,), cfg.dtype, 0.5)
+    if positions is None:
+        lens = [layout_length(l) for l in layouts_of(cfg, seed)]
+        positions = np.array([lens[m % len(lens)] - 1 + m // len(lens) for m in range(M)])
+    positions = np.asarray(positions, dtype=np.int32)
+    cs, sn = rope_rows(positions, d)
+    return HsrCase(cfg, embed, token_ids, h_prev, w_fc, b_fc, norm_weight, 1e-6, w_qkv, b_qkv,
+                   positions, cs, sn)
