@@ -5,6 +5,9 @@
  *   sparrow_draft_window_attn   draft model's text-anchored window attention
  *   sparrow_verify_attn         target model's verification attention
  *   sparrow_accept              lm_head GEMM -> per-row argmax -> greedy acceptance
+ * and, one step upstream of the draft attention,
+ *   sparrow_hsr_fc              draft input by hidden state reuse
+ *   sparrow_draft_qkv_append    draft layer norm / QKV / rotary step + K/V append
  *
  * C99, no C++ or HIP types.  "dev" pointers are device (HBM) addresses, "host"
  * pointers are ordinary host memory.
@@ -162,6 +165,60 @@ int sparrow_accept(int32_t dtype, const void *hidden_rows, const void *lm_head,
                    int32_t hidden, int32_t vocab, int32_t *target_ids, int32_t *accept_len,
                    int32_t *accept_path, int32_t *bonus_id, void *workspace,
                    size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Input of the draft model by hidden state reuse (Section "Visually-Aware
+ * Text-Anchored Window Attention via Hidden State Reuse", Eq. 1): for each of
+ * the M new tokens
+ *     z[m,:] = W_fc . concat(embed[token_ids[m],:], h_prev[m,:]) + b_fc
+ * i.e. the projection, back to the model width, of the token's embedding
+ * joined with the target model's hidden state of the previous step (which
+ * carries the visual context, so the draft never reads a visual token).
+ *
+ *  dtype      sparrow_dtype of embed, h_prev, w_fc, b_fc and z
+ *  embed      dev [vocab, hidden]
+ *  token_ids  dev int32 [M], values in [0, vocab) (out-of-range ids are clamped into the table)
+ *  h_prev     dev [M, hidden]
+ *  w_fc       dev [hidden, 2*hidden] row-major: columns 0..hidden-1 meet the embedding,
+ *             columns hidden..2*hidden-1 the hidden state
+ *  b_fc       dev [hidden] or NULL
+ *  z          dev out [M, hidden]
+ *  Limits: M <= 64, hidden a multiple of 8.  M = 0: SPARROW_OK, nothing enqueued.
+ */
+int sparrow_hsr_fc(int32_t dtype, const void *embed, const int32_t *token_ids, const void *h_prev,
+                   const void *w_fc, const void *b_fc, int32_t M, int32_t hidden, int32_t vocab,
+                   void *z, void *hip_stream);
+
+/*
+ * Input side of the draft's decoder layer for the M new tokens, producing
+ * what sparrow_draft_window_attn reads.  The paper gives no formula for the
+ * draft layer itself; it has the target's layer architecture, here the Qwen2
+ * family's: RMSNorm, a QKV projection with bias, rotate-half rotary embedding.
+ *     u = z / sqrt(mean(z^2) + eps) * norm_weight
+ *     y = W_qkv u + b_qkv          rows of W_qkv: Hq query heads, Hkv key heads, Hkv value heads
+ *     q, k rotated per head:  out[i] = x[i] cos[i] - x[i+d/2] sin[i],
+ *                             out[i+d/2] = x[i+d/2] cos[i] + x[i] sin[i]        (i < d/2)
+ * q goes to q_out; k and v of token m are written to row kv_rows[m] of the
+ * draft K/V cache (the append at the token's position).
+ *
+ *  desc        dtype of z, norm_weight, w_qkv, b_qkv, q_out and the cache; heads, head_dim and
+ *              the cache strides (scale is ignored)
+ *  z           dev [M, hidden]
+ *  norm_weight dev [hidden]
+ *  w_qkv       dev [(Hq + 2*Hkv)*d, hidden] row-major;  b_qkv dev [(Hq + 2*Hkv)*d] or NULL
+ *  rope_cos, rope_sin  dev float [M, d/2]: the rotary table rows of the tokens' positions
+ *                      (the caller owns the table; the library does not evaluate angles)
+ *  kv_rows     host int32 [M]: cache row of token m (cu_seqlens[b] + position), all distinct and
+ *              >= 0 (checked); that they lie inside the caches is the caller's precondition
+ *  q_out       dev out [M, Hq, d]
+ *  k_cache, v_cache  dev; row r, head c starts at element r*kv_stride_token + c*kv_stride_head
+ *  Limits: M <= 64, hidden a multiple of 8.  M = 0: SPARROW_OK, nothing enqueued.
+ */
+int sparrow_draft_qkv_append(const sparrow_attn_desc *desc, const void *z, const void *norm_weight,
+                             float eps, const void *w_qkv, const void *b_qkv,
+                             const float *rope_cos, const float *rope_sin,
+                             const int32_t *kv_rows, int32_t M, int32_t hidden, void *q_out,
+                             void *k_cache, void *v_cache, void *hip_stream);
 
 /* Thread-local description of the last error on this thread; "" if none. */
 const char *sparrow_last_error(void);

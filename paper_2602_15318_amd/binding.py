@@ -61,6 +61,12 @@ def _load() -> ctypes.CDLL:
     L.sparrow_accept.argtypes = [ctypes.c_int32, vp, vp, vp, vp, ctypes.c_int32, ctypes.c_int32,
                                  ctypes.c_int32, ctypes.c_int32, vp, vp, vp, vp, vp,
                                  ctypes.c_size_t, vp]
+    L.sparrow_hsr_fc.restype = ctypes.c_int
+    L.sparrow_hsr_fc.argtypes = [ctypes.c_int32, vp, vp, vp, vp, vp, ctypes.c_int32, ctypes.c_int32,
+                                 ctypes.c_int32, vp, vp]
+    L.sparrow_draft_qkv_append.restype = ctypes.c_int
+    L.sparrow_draft_qkv_append.argtypes = [dp, vp, vp, ctypes.c_float, vp, vp, vp, vp, i32p,
+                                           ctypes.c_int32, ctypes.c_int32, vp, vp, vp, vp]
     return L
 
 
@@ -210,3 +216,49 @@ def accept(hidden_rows, lm_head, draft_ids, parent, B: int, n_q: int, workspace=
                               0 if ws is None else ws.numel() * ws.element_size(),
                               _stream_ptr(stream)))
     return outputs
+
+
+def hsr_fc(embed, token_ids, h_prev, w_fc, b_fc=None, out=None, stream=None):
+    """sparrow_hsr_fc: z = FC(embed[token_ids] (+) h_prev).  embed [V,H]; token_ids int32 [M];
+    h_prev [M,H]; w_fc [H,2H]; b_fc [H] or None.  Returns z [M,H]."""
+    M, H = h_prev.shape
+    for t in (embed, h_prev, w_fc) + (() if b_fc is None else (b_fc,)):
+        if not t.is_contiguous() or t.dtype != h_prev.dtype:
+            raise ValueError("embed, h_prev, w_fc and b_fc must be contiguous and of one dtype")
+    if embed.shape[1] != H or tuple(w_fc.shape) != (H, 2 * H):
+        raise ValueError("embed must be [V, H] and w_fc [H, 2H]")
+    if token_ids.dtype != torch.int32 or token_ids.shape != (M,) or not token_ids.is_contiguous():
+        raise ValueError("token_ids must be a contiguous int32 tensor of M entries")
+    out = torch.empty_like(h_prev) if out is None else out
+    _check(lib.sparrow_hsr_fc(_dtype_code(h_prev), _ptr(embed), _ptr(token_ids), _ptr(h_prev),
+                              _ptr(w_fc), _ptr(b_fc), M, H, embed.shape[0], _ptr(out),
+                              _stream_ptr(stream)))
+    return out
+
+
+def draft_qkv_append(z, norm_weight, eps: float, w_qkv, b_qkv, rope_cos, rope_sin, kv_rows,
+                     n_q_heads: int, k_cache, v_cache, q_out=None, stream=None):
+    """sparrow_draft_qkv_append.  z [M,H]; w_qkv [(Hq+2Hkv)d, H]; rope_cos/sin float32 [M,d/2];
+    kv_rows host int32 [M]; k_cache, v_cache [T,Hkv,d] (written in place).  Returns q [M,Hq,d]."""
+    M, H = z.shape
+    Hkv, d = k_cache.shape[1], k_cache.shape[2]
+    if k_cache.stride(2) != 1 or v_cache.stride() != k_cache.stride() or v_cache.shape != k_cache.shape:
+        raise ValueError("k_cache and v_cache must be [T, Hkv, d] with identical strides and a contiguous d")
+    for t in (z, norm_weight, w_qkv) + (() if b_qkv is None else (b_qkv,)):
+        if not t.is_contiguous() or t.dtype != z.dtype:
+            raise ValueError("z, norm_weight, w_qkv and b_qkv must be contiguous and of one dtype")
+    if tuple(w_qkv.shape) != ((n_q_heads + 2 * Hkv) * d, H):
+        raise ValueError("w_qkv must be [(Hq + 2 Hkv) d, H]")
+    for t in (rope_cos, rope_sin):
+        if t.dtype != torch.float32 or tuple(t.shape) != (M, d // 2) or not t.is_contiguous():
+            raise ValueError("rope_cos and rope_sin must be contiguous float32 [M, d/2]")
+    rows = _host_i32(kv_rows)
+    if rows.shape != (M,):
+        raise ValueError("kv_rows must have M entries")
+    q_out = torch.empty((M, n_q_heads, d), dtype=z.dtype, device=z.device) if q_out is None else q_out
+    desc = AttnDesc(_dtype_code(z), n_q_heads, Hkv, d, 0.0, k_cache.stride(0), k_cache.stride(1))
+    _check(lib.sparrow_draft_qkv_append(ctypes.byref(desc), _ptr(z), _ptr(norm_weight), float(eps),
+                                        _ptr(w_qkv), _ptr(b_qkv), _ptr(rope_cos), _ptr(rope_sin),
+                                        _i32p(rows), M, H, _ptr(q_out), _ptr(k_cache),
+                                        _ptr(v_cache), _stream_ptr(stream)))
+    return q_out

@@ -1,0 +1,355 @@
+// Input side of the draft model: hidden-state-reuse projection (Eq. 1) and the draft layer's
+// RMSNorm / QKV / rotary step with the K/V append.  gfx950.
+//
+// Both are skinny GEMMs (at most 64 activation rows against a 51 MB and a 33 MB weight matrix at
+// Qwen2.5-VL-7B shape), bound by the weight stream like lm_head and built the same way:
+//   - one workgroup per tile of 16 weight rows (grid.y = blocks of 16 activation rows);
+//   - wavefront w owns the 512-wide k-slices w, w + NW, ...: every load instruction reads the
+//     slice of one weight row (1 KB contiguous), 16 loads in flight, staged through a private,
+//     XOR-swizzled 16 KB LDS buffer into the A operand of v_mfma_f32_16x16x32_bf16; the B operand
+//     is the wavefront's slice of the activation rows, held in registers;
+//   - the partial sums of the wavefronts meet in LDS and wavefront 0 runs the epilogue.
+// For the QKV step the tile's 16 weight rows are features f..f+7 and f+d/2..f+d/2+7 of one head,
+// so both halves of every rotary pair sit in the same tile (lanes l and l^32 of the result);
+// RMSNorm is folded in: gamma multiplies the activations on their way into the B operand, the
+// row's 1/rms (from the squares each wavefront sees in its own slices) scales the result.
+// Other shapes and fp32 run plain-ALU kernels (one wavefront per output feature or rotary pair).
+#include "common.hpp"
+#include "hsr_input.hpp"
+
+namespace sparrow {
+
+namespace {
+
+constexpr int kSlice = 512;               // k elements per wavefront slice (1 KB of bf16)
+
+// ---------------------------------------------------------------------------------------------
+// shared main loop: returns in wavefront 0 the tile's results, D[4*c4 + i][n] = sum over K of
+// W[wrow(4*c4 + i)][k] * x[row0 + n][k], lane = n + 16*c4; *ssq = sum of x[row0 + n][k]^2 (kNorm).
+// XLoad: x(m, k) -> pointer to 8 consecutive bf16 of activation row m at column k (k % 8 == 0).
+// ---------------------------------------------------------------------------------------------
+template <int NW, int SPW, bool kNorm, class WRow, class XLoad>
+__device__ __forceinline__ f32x4 skinny_tile(const bf16_t *W, int K, WRow wrow, XLoad xload,
+                                             const bf16_t *gamma, int row0, int M,
+                                             unsigned char *smem, float *ssq_out) {
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int n = lane & 15, c4 = lane >> 4;
+  unsigned char *stg = smem + w * 16384;
+  f32x4 *red = reinterpret_cast<f32x4 *>(smem + NW * 16384);          // [NW][64]
+  float *ssq_lds = reinterpret_cast<float *>(smem + NW * 16384 + NW * 1024);   // [NW][16]
+
+  u32x4 buf[16];
+  auto issue = [&](int s) {
+#pragma unroll
+    for (int r = 0; r < 16; ++r)
+      buf[r] = __builtin_nontemporal_load(
+          (const u32x4 *)(W + (int64_t)wrow(r) * K + kSlice * s + 8 * lane));
+  };
+  const int m = row0 + n;
+  const bool m_ok = m < M;
+  bf16x8 hreg[16];
+  float ssq = 0.f;
+  auto load_x = [&](int s) {
+#pragma unroll
+    for (int ks = 0; ks < 16; ++ks) {
+      const int k = kSlice * s + 32 * ks + 8 * c4;
+      u32x4 v = *(const u32x4 *)xload(m_ok ? m : 0, k);
+      if (!m_ok) v = (u32x4){0u, 0u, 0u, 0u};
+      if (kNorm) {
+        const u32x4 g = *(const u32x4 *)(gamma + k);
+        float xf[8], gf[8];
+        Elem<bf16_t>::unpack(v, xf);
+        Elem<bf16_t>::unpack(g, gf);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) ssq = fmaf(xf[e], xf[e], ssq);
+        v = (u32x4){pack_bf16x2(xf[0] * gf[0], xf[1] * gf[1]), pack_bf16x2(xf[2] * gf[2], xf[3] * gf[3]),
+                    pack_bf16x2(xf[4] * gf[4], xf[5] * gf[5]), pack_bf16x2(xf[6] * gf[6], xf[7] * gf[7])};
+      }
+      hreg[ks] = __builtin_bit_cast(bf16x8, v);
+    }
+  };
+
+  issue(w);
+  load_x(w);
+  f32x4 acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
+  const int a_base = n * 1024;            // A read: tile row n, 16-byte chunk 4*ks + c4
+#pragma unroll
+  for (int i = 0; i < SPW; ++i) {
+    // lane l of load r holds chunk l of row r; stored at chunk (l & ~15) | ((l & 15) ^ r) so that
+    // the A reads (16 rows, same chunk) spread over all banks
+#pragma unroll
+    for (int r = 0; r < 16; ++r)
+      *reinterpret_cast<u32x4 *>(stg + r * 1024 + (((lane & ~15) | ((lane & 15) ^ r)) << 4)) = buf[r];
+    if (i + 1 < SPW) issue(w + (i + 1) * NW);
+#pragma unroll
+    for (int ks = 0; ks < 16; ks += 2) {
+      const int ch0 = 4 * ks + c4, ch1 = ch0 + 4;
+      const bf16x8 a0 = *reinterpret_cast<const bf16x8 *>(stg + a_base + (((ch0 & ~15) | ((ch0 & 15) ^ n)) << 4));
+      const bf16x8 a1 = *reinterpret_cast<const bf16x8 *>(stg + a_base + (((ch1 & ~15) | ((ch1 & 15) ^ n)) << 4));
+      acc0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0, hreg[ks], acc0, 0, 0, 0);
+      acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, hreg[ks + 1], acc1, 0, 0, 0);
+    }
+    if (i + 1 < SPW) load_x(w + (i + 1) * NW);
+  }
+  red[w * 64 + lane] = acc0 + acc1;
+  if (kNorm) {
+    ssq += lane_xor<16>(ssq, lane);
+    ssq += lane_xor<32>(ssq, lane);       // all four k-chunk lanes of row n now hold the slice sum
+    if (c4 == 0) ssq_lds[w * 16 + n] = ssq;
+  }
+  __syncthreads();
+  f32x4 sum = {0.f, 0.f, 0.f, 0.f};
+  if (w == 0) {
+    sum = red[lane];
+#pragma unroll
+    for (int ww = 1; ww < NW; ++ww) sum += red[ww * 64 + lane];
+    if (kNorm) {
+      float s2 = 0.f;
+#pragma unroll
+      for (int ww = 0; ww < NW; ++ww) s2 += ssq_lds[ww * 16 + n];
+      *ssq_out = s2;
+    }
+  }
+  return sum;
+}
+
+constexpr int skinny_lds_bytes(int NW) { return NW * 16384 + NW * 1024 + NW * 64; }
+
+// ---------------------------------------------------------------------------------------------
+// Eq. 1: z = FC(e (+) h)
+// ---------------------------------------------------------------------------------------------
+template <int NW, int SPW>
+__global__ void __launch_bounds__(NW * 64)
+hsr_fc_mfma_kernel(HsrFcArgs a) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  const int tile = blockIdx.x, row0 = blockIdx.y * 16;
+  const int H = a.H;
+  const bf16_t *E = (const bf16_t *)a.embed, *Hp = (const bf16_t *)a.h_prev;
+  const int lane = threadIdx.x & 63, n = lane & 15, c4 = lane >> 4;
+  // the token id of this lane's activation row (clamped into the table)
+  const int m = row0 + n;
+  int tok = m < a.M ? a.token_ids[m] : 0;
+  tok = min(max(tok, 0), a.vocab - 1);
+  auto wrow = [&](int r) { return tile * 16 + r; };
+  // a slice lies entirely in one half of the concatenation (H is a multiple of the slice width)
+  auto xload = [&](int mm, int k) -> const bf16_t * {
+    return k < H ? E + (int64_t)tok * H + k : Hp + (int64_t)mm * H + (k - H);
+  };
+  float unused;
+  const f32x4 r = skinny_tile<NW, SPW, false>((const bf16_t *)a.w, 2 * H, wrow, xload, nullptr,
+                                               row0, a.M, smem, &unused);
+  if (threadIdx.x < 64 && m < a.M) {
+    const int f = tile * 16 + 4 * c4;
+    float b[4] = {0.f, 0.f, 0.f, 0.f};
+    if (a.bias != nullptr) {
+      const u32x2 bw = *(const u32x2 *)((const bf16_t *)a.bias + f);
+      b[0] = bf16lo_to_f32(bw.x); b[1] = bf16hi_to_f32(bw.x);
+      b[2] = bf16lo_to_f32(bw.y); b[3] = bf16hi_to_f32(bw.y);
+    }
+    const u32x2 o = {pack_bf16x2(r[0] + b[0], r[1] + b[1]), pack_bf16x2(r[2] + b[2], r[3] + b[3])};
+    *(u32x2 *)((bf16_t *)a.z + (int64_t)m * H + f) = o;
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// draft layer input: RMSNorm, QKV, rotary embedding, scatter
+// ---------------------------------------------------------------------------------------------
+template <int NW, int SPW>
+__global__ void __launch_bounds__(NW * 64)
+draft_qkv_mfma_kernel(DraftQkvArgs a) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  const int tile = blockIdx.x, row0 = blockIdx.y * 16;
+  const int H = a.H, d = a.d, half = d >> 1;
+  const int tiles_per_head = d >> 4;
+  const int hd = tile / tiles_per_head, j = tile - hd * tiles_per_head;   // head, 8-feature group
+  const int lane = threadIdx.x & 63, n = lane & 15, c4 = lane >> 4;
+  const int m = row0 + n;
+  const bf16_t *Z = (const bf16_t *)a.z;
+  // tile row r: feature 8j + (r & 7) of the head's first half for r < 8, its rotary partner
+  // (+ d/2) for r >= 8
+  auto wrow = [&](int r) { return hd * d + 8 * j + (r & 7) + (r >> 3) * half; };
+  auto xload = [&](int mm, int k) -> const bf16_t * { return Z + (int64_t)mm * H + k; };
+  float ssq = 0.f;
+  const f32x4 r = skinny_tile<NW, SPW, true>((const bf16_t *)a.w, H, wrow, xload,
+                                              (const bf16_t *)a.gamma, row0, a.M, smem, &ssq);
+  if (threadIdx.x >= 64) return;
+  // lane (n, c4), entry i: tile row 4*c4 + i -> feature f0 + i of half (c4 >> 1)
+  const int f0 = 8 * j + 4 * (c4 & 1);
+  const int hi = c4 >> 1;
+  const float rstd = __builtin_amdgcn_rsqf(ssq / (float)H + a.eps);
+  float y[4];
+  {
+    float b[4] = {0.f, 0.f, 0.f, 0.f};
+    if (a.bias != nullptr) {
+      const u32x2 bw = *(const u32x2 *)((const bf16_t *)a.bias + hd * d + hi * half + f0);
+      b[0] = bf16lo_to_f32(bw.x); b[1] = bf16hi_to_f32(bw.x);
+      b[2] = bf16lo_to_f32(bw.y); b[3] = bf16hi_to_f32(bw.y);
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) y[i] = fmaf(r[i], rstd, b[i]);
+  }
+  const bool is_v = hd >= a.Hq + a.Hkv;
+  float o[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const float partner = lane_xor<32>(y[i], lane);     // the other half of the rotary pair
+    o[i] = y[i];
+    if (!is_v && m < a.M) {
+      const float cs = a.rope_cos[(int64_t)m * half + f0 + i];
+      const float sn = a.rope_sin[(int64_t)m * half + f0 + i];
+      o[i] = hi ? fmaf(partner, sn, y[i] * cs) : fmaf(-partner, sn, y[i] * cs);
+    }
+  }
+  if (m >= a.M) return;
+  const u32x2 ow = {pack_bf16x2(o[0], o[1]), pack_bf16x2(o[2], o[3])};
+  const int feat = hi * half + f0;
+  if (hd < a.Hq) {
+    *(u32x2 *)((bf16_t *)a.q_out + ((int64_t)m * a.Hq + hd) * d + feat) = ow;
+  } else {
+    const int c = is_v ? hd - a.Hq - a.Hkv : hd - a.Hq;
+    bf16_t *base = (bf16_t *)(is_v ? a.v_cache : a.k_cache);
+    *(u32x2 *)(base + (int64_t)a.kv_rows[m] * a.stride_tok + (int64_t)c * a.stride_head + feat) = ow;
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// plain-ALU versions: any dtype, any H.  One wavefront per output feature (FC) or rotary pair.
+// ---------------------------------------------------------------------------------------------
+template <typename T>
+__global__ void __launch_bounds__(256)
+hsr_fc_generic_kernel(HsrFcArgs a) {
+  const int lane = threadIdx.x & 63;
+  const int nfeat = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (nfeat >= a.H) return;
+  const int H = a.H;
+  const T *W = (const T *)a.w + (int64_t)nfeat * 2 * H;
+  for (int row0 = 0; row0 < a.M; row0 += 16) {
+    float acc[16];
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+    for (int k = lane; k < 2 * H; k += 64) {
+      const float wv = Elem<T>::load(W + k);
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int m = row0 + r;
+        if (m < a.M) {
+          float x;
+          if (k < H) {
+            const int tok = min(max(a.token_ids[m], 0), a.vocab - 1);
+            x = Elem<T>::load((const T *)a.embed + (int64_t)tok * H + k);
+          } else {
+            x = Elem<T>::load((const T *)a.h_prev + (int64_t)m * H + (k - H));
+          }
+          acc[r] = fmaf(wv, x, acc[r]);
+        }
+      }
+    }
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const float s = wave_sum(acc[r]);
+      const int m = row0 + r;
+      if (lane == 0 && m < a.M) {
+        const float b = a.bias != nullptr ? Elem<T>::load((const T *)a.bias + nfeat) : 0.f;
+        Elem<T>::store((T *)a.z + (int64_t)m * H + nfeat, s + b);
+      }
+    }
+  }
+}
+
+template <typename T>
+__global__ void __launch_bounds__(256)
+draft_qkv_generic_kernel(DraftQkvArgs a) {
+  const int lane = threadIdx.x & 63;
+  const int half = a.d >> 1;
+  const int pair = blockIdx.x * 4 + (threadIdx.x >> 6);      // (head, feature of the first half)
+  const int n_heads = a.Hq + 2 * a.Hkv;
+  if (pair >= n_heads * half) return;
+  const int hd = pair / half, f = pair - hd * half;
+  const int H = a.H;
+  const T *W0 = (const T *)a.w + ((int64_t)hd * a.d + f) * H;
+  const T *W1 = W0 + (int64_t)half * H;
+  const bool is_v = hd >= a.Hq + a.Hkv;
+  for (int m = 0; m < a.M; ++m) {
+    const T *z = (const T *)a.z + (int64_t)m * H;
+    float s0 = 0.f, s1 = 0.f, ssq = 0.f;
+    for (int k = lane; k < H; k += 64) {
+      const float x = Elem<T>::load(z + k);
+      const float u = x * Elem<T>::load((const T *)a.gamma + k);
+      ssq = fmaf(x, x, ssq);
+      s0 = fmaf(Elem<T>::load(W0 + k), u, s0);
+      s1 = fmaf(Elem<T>::load(W1 + k), u, s1);
+    }
+    s0 = wave_sum(s0); s1 = wave_sum(s1); ssq = wave_sum(ssq);
+    if (lane != 0) continue;
+    const float rstd = 1.0f / sqrtf(ssq / (float)H + a.eps);
+    float y0 = s0 * rstd, y1 = s1 * rstd;
+    if (a.bias != nullptr) {
+      y0 += Elem<T>::load((const T *)a.bias + hd * a.d + f);
+      y1 += Elem<T>::load((const T *)a.bias + hd * a.d + f + half);
+    }
+    float o0 = y0, o1 = y1;
+    if (!is_v) {
+      const float cs = a.rope_cos[(int64_t)m * half + f], sn = a.rope_sin[(int64_t)m * half + f];
+      o0 = y0 * cs - y1 * sn;
+      o1 = y1 * cs + y0 * sn;
+    }
+    T *dst;
+    if (hd < a.Hq) {
+      dst = (T *)a.q_out + ((int64_t)m * a.Hq + hd) * a.d;
+    } else {
+      const int c = is_v ? hd - a.Hq - a.Hkv : hd - a.Hq;
+      dst = (T *)(is_v ? a.v_cache : a.k_cache) + (int64_t)a.kv_rows[m] * a.stride_tok +
+            (int64_t)c * a.stride_head;
+    }
+    Elem<T>::store(dst + f, o0);
+    Elem<T>::store(dst + f + half, o1);
+  }
+}
+
+template <auto kKern, class Args>
+hipError_t launch_skinny(int lds, dim3 grid, int threads, const Args &a, hipStream_t st) {
+  // more than 64 KB of dynamic LDS has to be allowed once per kernel
+  static const hipError_t attr = hipFuncSetAttribute(
+      (const void *)kKern, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+  if (attr != hipSuccess) return attr;
+  hipLaunchKernelGGL(kKern, grid, dim3(threads), lds, st, a);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+// The matrix-core kernels are instantiated for 7 and 8 slices of 512 (H = 3584, 4096).
+bool hsr_mfma_supported(int dtype, int H) {
+  return dtype == SPARROW_BF16 && (H == 7 * kSlice || H == 8 * kSlice);
+}
+
+hipError_t launch_hsr_fc(int dtype, const HsrFcArgs &a, hipStream_t st) {
+  const int rbs = (a.M + 15) / 16;
+  if (hsr_mfma_supported(dtype, a.H)) {
+    const dim3 grid(a.H / 16, rbs);
+    // K = 2H: two slices per wavefront
+    if (a.H == 7 * kSlice) return launch_skinny<hsr_fc_mfma_kernel<7, 2>>(skinny_lds_bytes(7), grid, 7 * 64, a, st);
+    if (a.H == 8 * kSlice) return launch_skinny<hsr_fc_mfma_kernel<8, 2>>(skinny_lds_bytes(8), grid, 8 * 64, a, st);
+  }
+  const dim3 grid((a.H + 3) / 4);
+  if (dtype == SPARROW_BF16) hipLaunchKernelGGL(hsr_fc_generic_kernel<bf16_t>, grid, dim3(256), 0, st, a);
+  else hipLaunchKernelGGL(hsr_fc_generic_kernel<float>, grid, dim3(256), 0, st, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_draft_qkv(int dtype, const DraftQkvArgs &a, hipStream_t st) {
+  const int rbs = (a.M + 15) / 16;
+  const int n_heads = a.Hq + 2 * a.Hkv;
+  if (hsr_mfma_supported(dtype, a.H)) {
+    const dim3 grid(n_heads * (a.d / 16), rbs);
+    if (a.H == 7 * kSlice) return launch_skinny<draft_qkv_mfma_kernel<7, 1>>(skinny_lds_bytes(7), grid, 7 * 64, a, st);
+    if (a.H == 8 * kSlice) return launch_skinny<draft_qkv_mfma_kernel<8, 1>>(skinny_lds_bytes(8), grid, 8 * 64, a, st);
+  }
+  const dim3 grid((n_heads * (a.d / 2) + 3) / 4);
+  if (dtype == SPARROW_BF16) hipLaunchKernelGGL(draft_qkv_generic_kernel<bf16_t>, grid, dim3(256), 0, st, a);
+  else hipLaunchKernelGGL(draft_qkv_generic_kernel<float>, grid, dim3(256), 0, st, a);
+  return hipGetLastError();
+}
+
+}  // namespace sparrow

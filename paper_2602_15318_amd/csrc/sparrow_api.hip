@@ -10,6 +10,7 @@
 #include "../../include/sparrow.h"
 #include "accept.hpp"
 #include "draft_window_attn.hpp"
+#include "hsr_input.hpp"
 #include "verify_attn.hpp"
 
 namespace sparrow {
@@ -112,6 +113,69 @@ size_t verify_ws_bytes(const sparrow_attn_desc *d, int64_t max_slots, int32_t n_
 using namespace sparrow;
 
 extern "C" {
+
+// ------------------------------------------------------------------ draft input side
+int sparrow_hsr_fc(int32_t dtype, const void *embed, const int32_t *token_ids, const void *h_prev,
+                   const void *w_fc, const void *b_fc, int32_t M, int32_t hidden, int32_t vocab,
+                   void *z, void *hip_stream) {
+  g_err[0] = 0;
+  if (dtype != SPARROW_F32 && dtype != SPARROW_BF16)
+    return fail(SPARROW_ERR_UNSUPPORTED, "dtype %d is neither SPARROW_F32 nor SPARROW_BF16", dtype);
+  if (M < 0 || hidden <= 0 || vocab <= 0)
+    return fail(SPARROW_ERR_INVALID_ARG, "M = %d, hidden = %d, vocab = %d", M, hidden, vocab);
+  if (M == 0) return SPARROW_OK;
+  if (M > kHsrMaxRows) return fail(SPARROW_ERR_UNSUPPORTED, "M = %d exceeds %d rows", M, kHsrMaxRows);
+  if (hidden % 8 != 0) return fail(SPARROW_ERR_UNSUPPORTED, "hidden = %d is not a multiple of 8", hidden);
+  if (!embed || !token_ids || !h_prev || !w_fc || !z)
+    return fail(SPARROW_ERR_INVALID_ARG, "NULL pointer among embed/token_ids/h_prev/w_fc/z");
+  if (!aligned16(embed) || !aligned16(h_prev) || !aligned16(w_fc) || !aligned16(z) ||
+      (b_fc && !aligned16(b_fc)))
+    return fail(SPARROW_ERR_INVALID_ARG, "embed, h_prev, w_fc, b_fc and z must be 16-byte aligned");
+  HsrFcArgs a;
+  a.embed = embed; a.token_ids = token_ids; a.h_prev = h_prev; a.w = w_fc; a.bias = b_fc; a.z = z;
+  a.M = M; a.H = hidden; a.vocab = vocab;
+  const hipError_t e = launch_hsr_fc(dtype, a, (hipStream_t)hip_stream);
+  if (e != hipSuccess) return fail(SPARROW_ERR_DEVICE, "hsr_fc launch: %s", hipGetErrorString(e));
+  return SPARROW_OK;
+}
+
+int sparrow_draft_qkv_append(const sparrow_attn_desc *desc, const void *z, const void *norm_weight,
+                             float eps, const void *w_qkv, const void *b_qkv,
+                             const float *rope_cos, const float *rope_sin,
+                             const int32_t *kv_rows, int32_t M, int32_t hidden, void *q_out,
+                             void *k_cache, void *v_cache, void *hip_stream) {
+  g_err[0] = 0;
+  if (int rc = check_desc(desc)) return rc;
+  if (M < 0 || hidden <= 0) return fail(SPARROW_ERR_INVALID_ARG, "M = %d, hidden = %d", M, hidden);
+  if (M == 0) return SPARROW_OK;
+  if (M > kHsrMaxRows) return fail(SPARROW_ERR_UNSUPPORTED, "M = %d exceeds %d rows", M, kHsrMaxRows);
+  if (hidden % 8 != 0) return fail(SPARROW_ERR_UNSUPPORTED, "hidden = %d is not a multiple of 8", hidden);
+  if (!(eps >= 0.f) || std::isinf(eps)) return fail(SPARROW_ERR_INVALID_ARG, "eps must be finite and >= 0");
+  if (!z || !norm_weight || !w_qkv || !rope_cos || !rope_sin || !kv_rows || !q_out || !k_cache || !v_cache)
+    return fail(SPARROW_ERR_INVALID_ARG,
+                "NULL pointer among z/norm_weight/w_qkv/rope_cos/rope_sin/kv_rows/q_out/k_cache/v_cache");
+  if (!aligned16(z) || !aligned16(norm_weight) || !aligned16(w_qkv) || (b_qkv && !aligned16(b_qkv)) ||
+      !aligned16(q_out) || !aligned16(k_cache) || !aligned16(v_cache))
+    return fail(SPARROW_ERR_INVALID_ARG, "z, norm_weight, w_qkv, b_qkv, q_out and the caches must be 16-byte aligned");
+  DraftQkvArgs a;
+  for (int m = 0; m < M; ++m) {
+    if (kv_rows[m] < 0) return fail(SPARROW_ERR_INVALID_ARG, "kv_rows[%d] = %d is negative", m, kv_rows[m]);
+    for (int j = 0; j < m; ++j)
+      if (kv_rows[j] == kv_rows[m])
+        return fail(SPARROW_ERR_INVALID_ARG, "kv_rows[%d] and kv_rows[%d] name the same cache row %d", j, m, kv_rows[m]);
+    a.kv_rows[m] = kv_rows[m];
+  }
+  for (int m = M; m < kHsrMaxRows; ++m) a.kv_rows[m] = 0;
+  a.z = z; a.gamma = norm_weight; a.w = w_qkv; a.bias = b_qkv;
+  a.rope_cos = rope_cos; a.rope_sin = rope_sin;
+  a.q_out = q_out; a.k_cache = k_cache; a.v_cache = v_cache;
+  a.stride_tok = desc->kv_stride_token; a.stride_head = desc->kv_stride_head;
+  a.eps = eps; a.M = M; a.H = hidden;
+  a.Hq = desc->n_q_heads; a.Hkv = desc->n_kv_heads; a.d = desc->head_dim;
+  const hipError_t e = launch_draft_qkv(desc->dtype, a, (hipStream_t)hip_stream);
+  if (e != hipSuccess) return fail(SPARROW_ERR_DEVICE, "draft_qkv launch: %s", hipGetErrorString(e));
+  return SPARROW_OK;
+}
 
 const char *sparrow_last_error(void) { return g_err; }
 const char *sparrow_version(void) { return "0.1"; }
