@@ -171,6 +171,32 @@ def main() -> int:
     us_draft = time_graph(capture(draft_many), 20) / 28
     us_accept = time_graph(capture(accept), 20)
 
+    # draft input side (the step before the draft attention; not part of `value`): Eq. 1 projection
+    # and the draft layer's norm/QKV/rotary/append for the one new token.  Six distinct copies of
+    # the weights (0.5 GB) are cycled through so that no launch finds its weights in the 256 MB
+    # Infinity Cache, as in a real step, where 1.5 GB of KV cache pass between two draft steps.
+    hc = wl.hsr_case(cfg, args.seed, rows=1, embed=acase.lm_head)
+    n_copies = 6
+    w_fc = [dev(hc.w_fc, bf16) for _ in range(n_copies)]
+    w_qkv = [dev(hc.w_qkv, bf16) for _ in range(n_copies)]
+    h_tok, h_prev = dev(hc.token_ids), dev(hc.h_prev, bf16)
+    h_bfc, h_g, h_bqkv = dev(hc.b_fc, bf16), dev(hc.norm_weight, bf16), dev(hc.b_qkv, bf16)
+    h_cos, h_sin = dev(hc.rope_cos), dev(hc.rope_sin)
+    h_z = torch.empty_like(h_prev)
+    h_q = torch.empty_like(dq)
+    kv_row = np.array([int(dcase.cu_seqlens[1]) - 1], dtype=np.int32)
+    def fc_many():
+        for i in range(2 * n_copies):
+            sp.hsr_fc(lm_head, h_tok, h_prev, w_fc[i % n_copies], h_bfc, out=h_z)
+    def qkv_many():
+        for i in range(2 * n_copies):
+            sp.draft_qkv_append(h_z, h_g, hc.eps, w_qkv[i % n_copies], h_bqkv, h_cos, h_sin, kv_row,
+                                Hq, dk, dv, q_out=h_q)
+    us_fc = time_graph(capture(fc_many), 20) / (2 * n_copies)
+    us_qkv = time_graph(capture(qkv_many), 20) / (2 * n_copies)
+    bytes_fc = cfg.hidden * 2 * cfg.hidden * esz + 3 * cfg.hidden * esz
+    bytes_qkv = (Hq + 2 * Hkv) * d * cfg.hidden * esz + 2 * cfg.hidden * esz
+
     # dominant kernel: the split-context partial pass of verify attention (one launch per layer).
     # Timed alone, 28 distinct layers back to back in a graph (1.5 GB: no cache reuse), HIP events
     # on the launch stream.
@@ -211,6 +237,10 @@ def main() -> int:
         "draft_attn_us": round(us_draft, 3),
         "accept_us": round(us_accept, 2),
         "accept_gbps": round(bytes_accept / us_accept * 1e-3, 1),
+        "draft_input": {"note": "step before the draft attention, one new token; not in `value`",
+                        "hsr_fc_us": round(us_fc, 2), "hsr_fc_gbps": round(bytes_fc / us_fc * 1e-3, 1),
+                        "draft_qkv_append_us": round(us_qkv, 2),
+                        "draft_qkv_append_gbps": round(bytes_qkv / us_qkv * 1e-3, 1)},
         "roofline": {"bound": "hbm", "kernel": "verify_partial_mfma_kernel (split-context partial "
                                                "pass of verify attention, one layer per launch)",
                      "achieved": round(gbps_partial, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",

@@ -24,86 +24,107 @@ namespace {
 constexpr int kSlice = 512;               // k elements per wavefront slice (1 KB of bf16)
 
 // ---------------------------------------------------------------------------------------------
-// shared main loop: returns in wavefront 0 the tile's results, D[4*c4 + i][n] = sum over K of
-// W[wrow(4*c4 + i)][k] * x[row0 + n][k], lane = n + 16*c4; *ssq = sum of x[row0 + n][k]^2 (kNorm).
+// shared main loop over TPW tiles of 16 weight rows: leaves in wavefront 0 the tiles' results,
+// out[tp][i] = D[4*c4 + i][n] = sum over K of W[wrow(tp, 4*c4 + i)][k] * x[row0 + n][k], lane =
+// n + 16*c4; *ssq = sum of x[row0 + n][k]^2 (kNorm).  SPW = slices per wavefront (K / 512 / NW).
 // XLoad: x(m, k) -> pointer to 8 consecutive bf16 of activation row m at column k (k % 8 == 0).
 // ---------------------------------------------------------------------------------------------
-template <int NW, int SPW, bool kNorm, class WRow, class XLoad>
-__device__ __forceinline__ f32x4 skinny_tile(const bf16_t *W, int K, WRow wrow, XLoad xload,
-                                             const bf16_t *gamma, int row0, int M,
-                                             unsigned char *smem, float *ssq_out) {
+template <int NW, int SPW, int TPW, bool kNorm, class WRow, class XLoad>
+__device__ __forceinline__ void skinny_tile(const bf16_t *W, int K, WRow wrow, XLoad xload,
+                                            const bf16_t *gamma, int row0, int M,
+                                            unsigned char *smem, f32x4 *out, float *ssq_out) {
   const int tid = threadIdx.x, lane = tid & 63;
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int n = lane & 15, c4 = lane >> 4;
   unsigned char *stg = smem + w * 16384;
-  f32x4 *red = reinterpret_cast<f32x4 *>(smem + NW * 16384);          // [NW][64]
-  float *ssq_lds = reinterpret_cast<float *>(smem + NW * 16384 + NW * 1024);   // [NW][16]
+  f32x4 *red = reinterpret_cast<f32x4 *>(smem + NW * 16384);          // [TPW][NW][64]
+  float *ssq_lds = reinterpret_cast<float *>(smem + NW * 16384 + TPW * NW * 1024);   // [NW][16]
 
   u32x4 buf[16];
-  auto issue = [&](int s) {
+  // phase p = (slice p / TPW of this wavefront, tile p % TPW)
+  auto issue = [&](int p) {
+    const int s = w + (p / TPW) * NW, tp = p % TPW;
 #pragma unroll
     for (int r = 0; r < 16; ++r)
       buf[r] = __builtin_nontemporal_load(
-          (const u32x4 *)(W + (int64_t)wrow(r) * K + kSlice * s + 8 * lane));
+          (const u32x4 *)(W + (int64_t)wrow(tp, r) * K + kSlice * s + 8 * lane));
   };
   const int m = row0 + n;
   const bool m_ok = m < M;
   bf16x8 hreg[16];
   float ssq = 0.f;
   auto load_x = [&](int s) {
+    // all loads first (raw activations, and gamma if the norm is folded in), then the conversion
+    // in place: the raw registers become the B operands
+    u32x4 xr[16], gr[16];
 #pragma unroll
     for (int ks = 0; ks < 16; ++ks) {
       const int k = kSlice * s + 32 * ks + 8 * c4;
-      u32x4 v = *(const u32x4 *)xload(m_ok ? m : 0, k);
+      xr[ks] = *(const u32x4 *)xload(m_ok ? m : 0, k);
+      if (kNorm) gr[ks] = *(const u32x4 *)(gamma + k);
+    }
+    if (kNorm) __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int ks = 0; ks < 16; ++ks) {
+      u32x4 v = xr[ks];
       if (!m_ok) v = (u32x4){0u, 0u, 0u, 0u};
       if (kNorm) {
-        const u32x4 g = *(const u32x4 *)(gamma + k);
         float xf[8], gf[8];
         Elem<bf16_t>::unpack(v, xf);
-        Elem<bf16_t>::unpack(g, gf);
+        Elem<bf16_t>::unpack(gr[ks], gf);
 #pragma unroll
         for (int e = 0; e < 8; ++e) ssq = fmaf(xf[e], xf[e], ssq);
         v = (u32x4){pack_bf16x2(xf[0] * gf[0], xf[1] * gf[1]), pack_bf16x2(xf[2] * gf[2], xf[3] * gf[3]),
                     pack_bf16x2(xf[4] * gf[4], xf[5] * gf[5]), pack_bf16x2(xf[6] * gf[6], xf[7] * gf[7])};
       }
       hreg[ks] = __builtin_bit_cast(bf16x8, v);
+      // one k-step at a time: unpacked, all 16 would need as many registers as the kernel has
+      if (kNorm) __builtin_amdgcn_sched_barrier(0);
     }
   };
 
-  issue(w);
+  issue(0);
   load_x(w);
-  f32x4 acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
+  f32x4 acc[TPW][2];
+#pragma unroll
+  for (int tp = 0; tp < TPW; ++tp) acc[tp][0] = acc[tp][1] = (f32x4){0.f, 0.f, 0.f, 0.f};
   const int a_base = n * 1024;            // A read: tile row n, 16-byte chunk 4*ks + c4
 #pragma unroll
-  for (int i = 0; i < SPW; ++i) {
+  for (int p = 0; p < SPW * TPW; ++p) {
+    const int tp = p % TPW;
     // lane l of load r holds chunk l of row r; stored at chunk (l & ~15) | ((l & 15) ^ r) so that
     // the A reads (16 rows, same chunk) spread over all banks
 #pragma unroll
     for (int r = 0; r < 16; ++r)
       *reinterpret_cast<u32x4 *>(stg + r * 1024 + (((lane & ~15) | ((lane & 15) ^ r)) << 4)) = buf[r];
-    if (i + 1 < SPW) issue(w + (i + 1) * NW);
+    if (p + 1 < SPW * TPW) issue(p + 1);
 #pragma unroll
     for (int ks = 0; ks < 16; ks += 2) {
       const int ch0 = 4 * ks + c4, ch1 = ch0 + 4;
       const bf16x8 a0 = *reinterpret_cast<const bf16x8 *>(stg + a_base + (((ch0 & ~15) | ((ch0 & 15) ^ n)) << 4));
       const bf16x8 a1 = *reinterpret_cast<const bf16x8 *>(stg + a_base + (((ch1 & ~15) | ((ch1 & 15) ^ n)) << 4));
-      acc0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0, hreg[ks], acc0, 0, 0, 0);
-      acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, hreg[ks + 1], acc1, 0, 0, 0);
+      acc[tp][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0, hreg[ks], acc[tp][0], 0, 0, 0);
+      acc[tp][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, hreg[ks + 1], acc[tp][1], 0, 0, 0);
     }
-    if (i + 1 < SPW) load_x(w + (i + 1) * NW);
+    // next slice of the activations once the last tile of this slice is done
+    if (tp == TPW - 1 && p + 1 < SPW * TPW) load_x(w + ((p + 1) / TPW) * NW);
   }
-  red[w * 64 + lane] = acc0 + acc1;
+#pragma unroll
+  for (int tp = 0; tp < TPW; ++tp) red[(tp * NW + w) * 64 + lane] = acc[tp][0] + acc[tp][1];
   if (kNorm) {
     ssq += lane_xor<16>(ssq, lane);
     ssq += lane_xor<32>(ssq, lane);       // all four k-chunk lanes of row n now hold the slice sum
     if (c4 == 0) ssq_lds[w * 16 + n] = ssq;
   }
   __syncthreads();
-  f32x4 sum = {0.f, 0.f, 0.f, 0.f};
   if (w == 0) {
-    sum = red[lane];
 #pragma unroll
-    for (int ww = 1; ww < NW; ++ww) sum += red[ww * 64 + lane];
+    for (int tp = 0; tp < TPW; ++tp) {
+      f32x4 sum = red[(tp * NW) * 64 + lane];
+#pragma unroll
+      for (int ww = 1; ww < NW; ++ww) sum += red[(tp * NW + ww) * 64 + lane];
+      out[tp] = sum;
+    }
     if (kNorm) {
       float s2 = 0.f;
 #pragma unroll
@@ -111,10 +132,9 @@ __device__ __forceinline__ f32x4 skinny_tile(const bf16_t *W, int K, WRow wrow, 
       *ssq_out = s2;
     }
   }
-  return sum;
 }
 
-constexpr int skinny_lds_bytes(int NW) { return NW * 16384 + NW * 1024 + NW * 64; }
+constexpr int skinny_lds_bytes(int NW, int TPW) { return NW * 16384 + TPW * NW * 1024 + NW * 64; }
 
 // ---------------------------------------------------------------------------------------------
 // Eq. 1: z = FC(e (+) h)
@@ -131,14 +151,15 @@ hsr_fc_mfma_kernel(HsrFcArgs a) {
   const int m = row0 + n;
   int tok = m < a.M ? a.token_ids[m] : 0;
   tok = min(max(tok, 0), a.vocab - 1);
-  auto wrow = [&](int r) { return tile * 16 + r; };
+  auto wrow = [&](int, int r) { return tile * 16 + r; };
   // a slice lies entirely in one half of the concatenation (H is a multiple of the slice width)
   auto xload = [&](int mm, int k) -> const bf16_t * {
     return k < H ? E + (int64_t)tok * H + k : Hp + (int64_t)mm * H + (k - H);
   };
   float unused;
-  const f32x4 r = skinny_tile<NW, SPW, false>((const bf16_t *)a.w, 2 * H, wrow, xload, nullptr,
-                                               row0, a.M, smem, &unused);
+  f32x4 r;
+  skinny_tile<NW, SPW, 1, false>((const bf16_t *)a.w, 2 * H, wrow, xload, nullptr, row0, a.M, smem,
+                                 &r, &unused);
   if (threadIdx.x < 64 && m < a.M) {
     const int f = tile * 16 + 4 * c4;
     float b[4] = {0.f, 0.f, 0.f, 0.f};
@@ -158,58 +179,77 @@ hsr_fc_mfma_kernel(HsrFcArgs a) {
 template <int NW, int SPW>
 __global__ void __launch_bounds__(NW * 64)
 draft_qkv_mfma_kernel(DraftQkvArgs a) {
+  constexpr int TPW = 2;        // tiles per workgroup: blockIdx.x and blockIdx.x + gridDim.x
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  const int tile = blockIdx.x, row0 = blockIdx.y * 16;
+  const int row0 = blockIdx.y * 16;
   const int H = a.H, d = a.d, half = d >> 1;
   const int tiles_per_head = d >> 4;
-  const int hd = tile / tiles_per_head, j = tile - hd * tiles_per_head;   // head, 8-feature group
   const int lane = threadIdx.x & 63, n = lane & 15, c4 = lane >> 4;
   const int m = row0 + n;
+  const bool m_ok = m < a.M;
   const bf16_t *Z = (const bf16_t *)a.z;
-  // tile row r: feature 8j + (r & 7) of the head's first half for r < 8, its rotary partner
-  // (+ d/2) for r >= 8
-  auto wrow = [&](int r) { return hd * d + 8 * j + (r & 7) + (r >> 3) * half; };
+  // tile -> (head, group j of 8 features); tile row r: feature 8j + (r & 7) of the head's first
+  // half for r < 8, its rotary partner (+ d/2) for r >= 8
+  int hd[TPW], j[TPW];
+#pragma unroll
+  for (int tp = 0; tp < TPW; ++tp) {
+    const int tile = blockIdx.x + tp * gridDim.x;
+    hd[tp] = tile / tiles_per_head;
+    j[tp] = tile - hd[tp] * tiles_per_head;
+  }
+  auto wrow = [&](int tp, int r) { return hd[tp] * d + 8 * j[tp] + (r & 7) + (r >> 3) * half; };
   auto xload = [&](int mm, int k) -> const bf16_t * { return Z + (int64_t)mm * H + k; };
-  float ssq = 0.f;
-  const f32x4 r = skinny_tile<NW, SPW, true>((const bf16_t *)a.w, H, wrow, xload,
-                                              (const bf16_t *)a.gamma, row0, a.M, smem, &ssq);
-  if (threadIdx.x >= 64) return;
-  // lane (n, c4), entry i: tile row 4*c4 + i -> feature f0 + i of half (c4 >> 1)
-  const int f0 = 8 * j + 4 * (c4 & 1);
+  // lane (n, c4), entry i of a tile's result: tile row 4*c4 + i -> feature f0 + i of half `hi`
   const int hi = c4 >> 1;
+  // epilogue operands, fetched ahead of the weight stream: bias, the token's rotary row, its
+  // cache row (the table is a kernel argument, read with uniform indices)
+  u32x2 bw[TPW];
+  f32x4 cs[TPW], sn[TPW];
+#pragma unroll
+  for (int tp = 0; tp < TPW; ++tp) {
+    const int f0 = 8 * j[tp] + 4 * (c4 & 1);
+    bw[tp] = (u32x2){0u, 0u};
+    if (a.bias != nullptr) bw[tp] = *(const u32x2 *)((const bf16_t *)a.bias + hd[tp] * d + hi * half + f0);
+    cs[tp] = *(const f32x4 *)(a.rope_cos + (int64_t)(m_ok ? m : 0) * half + f0);
+    sn[tp] = *(const f32x4 *)(a.rope_sin + (int64_t)(m_ok ? m : 0) * half + f0);
+  }
+  int kv_row = 0;
+#pragma unroll
+  for (int mm = 0; mm < 16; ++mm) {
+    const int r = a.kv_rows[min(row0 + mm, kHsrMaxRows - 1)];
+    if (n == mm) kv_row = r;
+  }
+
+  float ssq = 0.f;
+  f32x4 res[TPW];
+  skinny_tile<NW, SPW, TPW, true>((const bf16_t *)a.w, H, wrow, xload, (const bf16_t *)a.gamma,
+                                  row0, a.M, smem, res, &ssq);
+  if (threadIdx.x >= 64) return;
   const float rstd = __builtin_amdgcn_rsqf(ssq / (float)H + a.eps);
-  float y[4];
-  {
-    float b[4] = {0.f, 0.f, 0.f, 0.f};
-    if (a.bias != nullptr) {
-      const u32x2 bw = *(const u32x2 *)((const bf16_t *)a.bias + hd * d + hi * half + f0);
-      b[0] = bf16lo_to_f32(bw.x); b[1] = bf16hi_to_f32(bw.x);
-      b[2] = bf16lo_to_f32(bw.y); b[3] = bf16hi_to_f32(bw.y);
-    }
 #pragma unroll
-    for (int i = 0; i < 4; ++i) y[i] = fmaf(r[i], rstd, b[i]);
-  }
-  const bool is_v = hd >= a.Hq + a.Hkv;
-  float o[4];
+  for (int tp = 0; tp < TPW; ++tp) {
+    const int f0 = 8 * j[tp] + 4 * (c4 & 1);
+    const float b[4] = {bf16lo_to_f32(bw[tp].x), bf16hi_to_f32(bw[tp].x),
+                        bf16lo_to_f32(bw[tp].y), bf16hi_to_f32(bw[tp].y)};
+    const bool is_v = hd[tp] >= a.Hq + a.Hkv;
+    float o[4];
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const float partner = lane_xor<32>(y[i], lane);     // the other half of the rotary pair
-    o[i] = y[i];
-    if (!is_v && m < a.M) {
-      const float cs = a.rope_cos[(int64_t)m * half + f0 + i];
-      const float sn = a.rope_sin[(int64_t)m * half + f0 + i];
-      o[i] = hi ? fmaf(partner, sn, y[i] * cs) : fmaf(-partner, sn, y[i] * cs);
+    for (int i = 0; i < 4; ++i) {
+      const float y = fmaf(res[tp][i], rstd, b[i]);
+      const float partner = lane_xor<32>(y, lane);      // the other half of the rotary pair
+      o[i] = y;
+      if (!is_v) o[i] = hi ? fmaf(partner, sn[tp][i], y * cs[tp][i]) : fmaf(-partner, sn[tp][i], y * cs[tp][i]);
     }
-  }
-  if (m >= a.M) return;
-  const u32x2 ow = {pack_bf16x2(o[0], o[1]), pack_bf16x2(o[2], o[3])};
-  const int feat = hi * half + f0;
-  if (hd < a.Hq) {
-    *(u32x2 *)((bf16_t *)a.q_out + ((int64_t)m * a.Hq + hd) * d + feat) = ow;
-  } else {
-    const int c = is_v ? hd - a.Hq - a.Hkv : hd - a.Hq;
-    bf16_t *base = (bf16_t *)(is_v ? a.v_cache : a.k_cache);
-    *(u32x2 *)(base + (int64_t)a.kv_rows[m] * a.stride_tok + (int64_t)c * a.stride_head + feat) = ow;
+    if (!m_ok) continue;
+    const u32x2 ow = {pack_bf16x2(o[0], o[1]), pack_bf16x2(o[2], o[3])};
+    const int feat = hi * half + f0;
+    if (hd[tp] < a.Hq) {
+      *(u32x2 *)((bf16_t *)a.q_out + ((int64_t)m * a.Hq + hd[tp]) * d + feat) = ow;
+    } else {
+      const int c = is_v ? hd[tp] - a.Hq - a.Hkv : hd[tp] - a.Hq;
+      bf16_t *base = (bf16_t *)(is_v ? a.v_cache : a.k_cache);
+      *(u32x2 *)(base + (int64_t)kv_row * a.stride_tok + (int64_t)c * a.stride_head + feat) = ow;
+    }
   }
 }
 
@@ -329,8 +369,8 @@ hipError_t launch_hsr_fc(int dtype, const HsrFcArgs &a, hipStream_t st) {
   if (hsr_mfma_supported(dtype, a.H)) {
     const dim3 grid(a.H / 16, rbs);
     // K = 2H: two slices per wavefront
-    if (a.H == 7 * kSlice) return launch_skinny<hsr_fc_mfma_kernel<7, 2>>(skinny_lds_bytes(7), grid, 7 * 64, a, st);
-    if (a.H == 8 * kSlice) return launch_skinny<hsr_fc_mfma_kernel<8, 2>>(skinny_lds_bytes(8), grid, 8 * 64, a, st);
+    if (a.H == 7 * kSlice) return launch_skinny<hsr_fc_mfma_kernel<7, 2>>(skinny_lds_bytes(7, 1), grid, 7 * 64, a, st);
+    if (a.H == 8 * kSlice) return launch_skinny<hsr_fc_mfma_kernel<8, 2>>(skinny_lds_bytes(8, 1), grid, 8 * 64, a, st);
   }
   const dim3 grid((a.H + 3) / 4);
   if (dtype == SPARROW_BF16) hipLaunchKernelGGL(hsr_fc_generic_kernel<bf16_t>, grid, dim3(256), 0, st, a);
@@ -342,9 +382,11 @@ hipError_t launch_draft_qkv(int dtype, const DraftQkvArgs &a, hipStream_t st) {
   const int rbs = (a.M + 15) / 16;
   const int n_heads = a.Hq + 2 * a.Hkv;
   if (hsr_mfma_supported(dtype, a.H)) {
-    const dim3 grid(n_heads * (a.d / 16), rbs);
-    if (a.H == 7 * kSlice) return launch_skinny<draft_qkv_mfma_kernel<7, 1>>(skinny_lds_bytes(7), grid, 7 * 64, a, st);
-    if (a.H == 8 * kSlice) return launch_skinny<draft_qkv_mfma_kernel<8, 1>>(skinny_lds_bytes(8), grid, 8 * 64, a, st);
+    // two tiles per workgroup (d / 16 tiles per head: an even number): 144 workgroups at 36 heads
+    // of 128 stay within one round on 256 compute units
+    const dim3 grid(n_heads * (a.d / 16) / 2, rbs);
+    if (a.H == 7 * kSlice) return launch_skinny<draft_qkv_mfma_kernel<7, 1>>(skinny_lds_bytes(7, 2), grid, 7 * 64, a, st);
+    if (a.H == 8 * kSlice) return launch_skinny<draft_qkv_mfma_kernel<8, 1>>(skinny_lds_bytes(8, 2), grid, 8 * 64, a, st);
   }
   const dim3 grid((n_heads * (a.d / 2) + 3) / 4);
   if (dtype == SPARROW_BF16) hipLaunchKernelGGL(draft_qkv_generic_kernel<bf16_t>, grid, dim3(256), 0, st, a);

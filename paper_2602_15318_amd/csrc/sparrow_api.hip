@@ -155,8 +155,10 @@ int sparrow_draft_qkv_append(const sparrow_attn_desc *desc, const void *z, const
     return fail(SPARROW_ERR_INVALID_ARG,
                 "NULL pointer among z/norm_weight/w_qkv/rope_cos/rope_sin/kv_rows/q_out/k_cache/v_cache");
   if (!aligned16(z) || !aligned16(norm_weight) || !aligned16(w_qkv) || (b_qkv && !aligned16(b_qkv)) ||
-      !aligned16(q_out) || !aligned16(k_cache) || !aligned16(v_cache))
-    return fail(SPARROW_ERR_INVALID_ARG, "z, norm_weight, w_qkv, b_qkv, q_out and the caches must be 16-byte aligned");
+      !aligned16(q_out) || !aligned16(k_cache) || !aligned16(v_cache) || !aligned16(rope_cos) ||
+      !aligned16(rope_sin))
+    return fail(SPARROW_ERR_INVALID_ARG,
+                "z, norm_weight, w_qkv, b_qkv, rope_cos, rope_sin, q_out and the caches must be 16-byte aligned");
   DraftQkvArgs a;
   for (int m = 0; m < M; ++m) {
     if (kv_rows[m] < 0) return fail(SPARROW_ERR_INVALID_ARG, "kv_rows[%d] = %d is negative", m, kv_rows[m]);
