@@ -49,6 +49,8 @@ def _load():
         _lib.oracle_hsr_fc.restype = None
         _lib.oracle_draft_qkv.restype = None
         _lib.oracle_rope_table.restype = None
+        _lib.oracle_kv_commit.restype = None
+        _lib.oracle_next_hidden.restype = None
     return _lib
 
 
@@ -221,3 +223,29 @@ def rope_table(positions, head_dim: int, theta: float = 1.0e6):
     lib.oracle_rope_table(_ptr(pos, _ip), ctypes.c_int(M), ctypes.c_int(head_dim),
                           ctypes.c_double(theta), _ptr(cs, _dp), _ptr(sn, _dp))
     return cs, sn
+
+
+def kv_commit(cache, cu_seqlens, n_q: int, accept_path, accept_len) -> np.ndarray:
+    """One layer's K or V cache [T, ...] after the accepted draft rows have been moved up behind
+    the context, in path order.  Returns a new float64 array of the same shape."""
+    lib = _load()
+    c = np.array(cache, dtype=np.float64, order="C", copy=True)
+    cu = _i32(cu_seqlens)
+    B = cu.shape[0] - 1
+    path, alen = _i32(accept_path).reshape(B, max(n_q, 0)), _i32(accept_len)
+    row_elems = int(np.prod(c.shape[1:]))
+    lib.oracle_kv_commit(_ptr(c, _dp), ctypes.c_int64(row_elems), _ptr(cu, _ip), ctypes.c_int(B),
+                         ctypes.c_int(n_q), _ptr(path, _ip), _ptr(alen, _ip))
+    return c
+
+
+def next_hidden(hidden, B: int, n_q: int, accept_path, accept_len) -> np.ndarray:
+    """[B, H] hidden rows of the last accepted nodes (row 0 of a sequence if none)."""
+    lib = _load()
+    h = _f64(hidden)
+    H = h.shape[1]
+    path, alen = _i32(accept_path).reshape(B, max(n_q, 0)), _i32(accept_len)
+    out = np.empty((B, H), dtype=np.float64)
+    lib.oracle_next_hidden(_ptr(h, _dp), ctypes.c_int(B), ctypes.c_int(n_q), ctypes.c_int(H),
+                           _ptr(path, _ip), _ptr(alen, _ip), _ptr(out, _dp))
+    return out

@@ -306,3 +306,45 @@ void oracle_rope_table(const int32_t *pos, int M, int d, double theta, double *r
             rope_sin[(int64_t)m * half + i] = sin(ang);
         }
 }
+
+/* ------------------------------------------------------------------------
+ * Post-accept commit (the step after greedy acceptance; the paper leaves the
+ * mechanics open, it follows from verifying a tree and reusing hidden states):
+ * the K/V rows of the accepted draft nodes become the next context rows, in
+ * path order, and the hidden state of the last accepted row is handed to the
+ * draft model for the next step (the h of Eq. 1).
+ *   cache  [T, row_elems] one layer's K or V as doubles; sequence b owns rows
+ *          cu[b] .. cu[b+1]-1 = L_b context rows then n_q draft rows
+ *   after the call row cu[b] + L_b + j holds what row cu[b] + L_b + path[b][j]
+ *   held before it, for j < accept_len[b]; every other row is unchanged.
+ * ------------------------------------------------------------------------ */
+void oracle_kv_commit(double *cache, int64_t row_elems, const int32_t *cu, int B, int n_q,
+                      const int32_t *accept_path, const int32_t *accept_len)
+{
+    double *tmp = (double *)malloc(sizeof(double) * (size_t)(n_q > 0 ? n_q : 1) * row_elems);
+    for (int b = 0; b < B; ++b) {
+        const int64_t first = (int64_t)cu[b + 1] - n_q;          /* first draft row */
+        const int len = accept_len[b];
+        for (int j = 0; j < len; ++j)                            /* read everything first */
+            memcpy(tmp + (int64_t)j * row_elems,
+                   cache + (first + accept_path[(int64_t)b * n_q + j]) * row_elems,
+                   sizeof(double) * row_elems);
+        for (int j = 0; j < len; ++j)
+            memcpy(cache + (first + j) * row_elems, tmp + (int64_t)j * row_elems,
+                   sizeof(double) * row_elems);
+    }
+    free(tmp);
+}
+
+/* Hidden row handed to the draft for the next step: the row of the last accepted node, or row 0
+ * of the sequence (the last accepted token of the previous step) if nothing was accepted.
+ *   hidden [B*(n_q+1), H], out [B, H] */
+void oracle_next_hidden(const double *hidden, int B, int n_q, int H, const int32_t *accept_path,
+                        const int32_t *accept_len, double *out)
+{
+    for (int b = 0; b < B; ++b) {
+        const int len = accept_len[b];
+        const int row = len > 0 ? 1 + accept_path[(int64_t)b * n_q + len - 1] : 0;
+        memcpy(out + (int64_t)b * H, hidden + ((int64_t)b * (n_q + 1) + row) * H, sizeof(double) * H);
+    }
+}
