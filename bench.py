@@ -197,6 +197,17 @@ def main() -> int:
     bytes_fc = cfg.hidden * 2 * cfg.hidden * esz + 3 * cfg.hidden * esz
     bytes_qkv = (Hq + 2 * Hkv) * d * cfg.hidden * esz + 2 * cfg.hidden * esz
 
+    # post-accept commit (the step after acceptance; not part of `value`): 4 accepted drafts of the
+    # chain, all 28 layers in one launch, plus the hidden row for the draft's next input
+    c_path = dev(np.array([[0, 1, 2, 3] + [-1] * (n_q - 4)], dtype=np.int32))
+    c_len = dev(np.array([4], dtype=np.int32))
+    c_next = torch.empty_like(h_prev)
+    ks_all, vs_all = [k for _, k, _ in layers], [v for _, _, v in layers]
+    def commit_many():
+        for _ in range(10):
+            sp.kv_commit(ks_all, vs_all, cu, n_q, c_path, c_len, hidden_rows=hidden, next_hidden=c_next)
+    us_commit = time_graph(capture(commit_many), 20) / 10
+
     # dominant kernel: the split-context partial pass of verify attention (one launch per layer).
     # Timed alone, 28 distinct layers back to back in a graph (1.5 GB: no cache reuse), HIP events
     # on the launch stream.
@@ -241,6 +252,7 @@ def main() -> int:
                         "hsr_fc_us": round(us_fc, 2), "hsr_fc_gbps": round(bytes_fc / us_fc * 1e-3, 1),
                         "draft_qkv_append_us": round(us_qkv, 2),
                         "draft_qkv_append_gbps": round(bytes_qkv / us_qkv * 1e-3, 1)},
+        "kv_commit_us": round(us_commit, 2),
         "roofline": {"bound": "hbm", "kernel": "verify_partial_mfma_kernel (split-context partial "
                                                "pass of verify attention, one layer per launch)",
                      "achieved": round(gbps_partial, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",

@@ -8,6 +8,8 @@
  * and, one step upstream of the draft attention,
  *   sparrow_hsr_fc              draft input by hidden state reuse
  *   sparrow_draft_qkv_append    draft layer norm / QKV / rotary step + K/V append
+ * and, one step downstream of the acceptance,
+ *   sparrow_kv_commit           accepted K/V rows moved behind the context, next hidden row
  *
  * C99, no C++ or HIP types.  "dev" pointers are device (HBM) addresses, "host"
  * pointers are ordinary host memory.
@@ -219,6 +221,32 @@ int sparrow_draft_qkv_append(const sparrow_attn_desc *desc, const void *z, const
                              const float *rope_cos, const float *rope_sin,
                              const int32_t *kv_rows, int32_t M, int32_t hidden, void *q_out,
                              void *k_cache, void *v_cache, void *hip_stream);
+
+/*
+ * Post-accept commit, the step after sparrow_accept (the paper leaves its
+ * mechanics open; it follows from verifying a draft tree against one KV cache
+ * and from reusing the target's hidden state, Eq. 1): in every layer, the K/V
+ * rows of the accepted draft nodes are moved up behind the context in path
+ * order, so that the sequence's cache is contiguous again,
+ *     row L_b + j  <-  row L_b + accept_path[b][j]     for j < accept_len[b],
+ * and the hidden row of the last accepted node (row 0 of the sequence if none
+ * was accepted) is copied out as the draft's next h.
+ *
+ *  desc        dtype, n_kv_heads, head_dim and the strides of every layer's K and V
+ *  k_layers, v_layers  host arrays [n_layers] of device pointers, the layout of sparrow_verify_attn
+ *  cu_seqlens  host int32 [B+1]: sequence b owns L_b context rows followed by n_q draft rows
+ *  accept_path dev int32 [B, n_q], accept_len dev int32 [B]: as written by sparrow_accept
+ *              (entries are clamped into [0, n_q) before use)
+ *  hidden_rows dev [B*(n_q+1), hidden] or NULL; next_hidden dev out [B, hidden] (required if
+ *              hidden_rows is given); hidden*element size a multiple of 16 bytes
+ *  Limits: n_layers <= 64, B <= 64, n_q <= 64.  B = 0 or n_layers = 0 with no hidden_rows: no-op.
+ *  The new sequence lengths (L_b + accept_len[b]) are the caller's bookkeeping.
+ */
+int sparrow_kv_commit(const sparrow_attn_desc *desc, void *const *k_layers, void *const *v_layers,
+                      int32_t n_layers, const int32_t *cu_seqlens, int32_t B, int32_t n_q,
+                      const int32_t *accept_path, const int32_t *accept_len,
+                      const void *hidden_rows, int32_t hidden, void *next_hidden,
+                      void *hip_stream);
 
 /* Thread-local description of the last error on this thread; "" if none. */
 const char *sparrow_last_error(void);

@@ -1,12 +1,12 @@
 """MI355X-native hot path of one Sparrow speculative-decoding step.
 
 Thin Python binding over the C-ABI library built from csrc/ (see include/sparrow.h):
-draft_window_attn, verify_attn and accept, plus hsr_fc and draft_qkv_append (the draft's input side).  All computation runs in the HIP kernels;
+draft_window_attn, verify_attn and accept, plus hsr_fc and draft_qkv_append (the draft's input side) and kv_commit (after acceptance).  All computation runs in the HIP kernels;
 PyTorch only provides device memory and streams.
 """
 __all__ = ["SparrowError", "accept", "accept_workspace_bytes", "draft_window_attn", "last_error",
            "library_path", "verify_attn", "verify_attn_workspace_bytes", "version", "AttnDesc",
-           "lib", "hsr_fc", "draft_qkv_append"]
+           "lib", "hsr_fc", "draft_qkv_append", "kv_commit"]
 
 
 def __getattr__(name):

@@ -67,6 +67,10 @@ def _load() -> ctypes.CDLL:
     L.sparrow_draft_qkv_append.restype = ctypes.c_int
     L.sparrow_draft_qkv_append.argtypes = [dp, vp, vp, ctypes.c_float, vp, vp, vp, vp, i32p,
                                            ctypes.c_int32, ctypes.c_int32, vp, vp, vp, vp]
+    L.sparrow_kv_commit.restype = ctypes.c_int
+    L.sparrow_kv_commit.argtypes = [dp, ctypes.POINTER(ctypes.c_void_p), ctypes.POINTER(ctypes.c_void_p),
+                                    ctypes.c_int32, i32p, ctypes.c_int32, ctypes.c_int32, vp, vp,
+                                    vp, ctypes.c_int32, vp, vp]
     return L
 
 
@@ -262,3 +266,41 @@ def draft_qkv_append(z, norm_weight, eps: float, w_qkv, b_qkv, rope_cos, rope_si
                                         _i32p(rows), M, H, _ptr(q_out), _ptr(k_cache),
                                         _ptr(v_cache), _stream_ptr(stream)))
     return q_out
+
+
+def kv_commit(k_layers, v_layers, cu_seqlens, n_q: int, accept_path, accept_len, hidden_rows=None,
+              next_hidden=None, stream=None):
+    """sparrow_kv_commit.  k_layers, v_layers: lists of [T,Hkv,d] tensors (moved in place);
+    accept_path int32 [B,n_q] and accept_len int32 [B] device tensors.  Returns next_hidden
+    ([B,H], or None without hidden_rows)."""
+    cu = _host_i32(cu_seqlens)
+    B = cu.shape[0] - 1
+    nl = len(k_layers)
+    if len(v_layers) != nl:
+        raise ValueError("k_layers and v_layers must have the same length")
+    for t in (accept_path, accept_len):
+        if t.dtype != torch.int32 or not t.is_contiguous():
+            raise ValueError("accept_path and accept_len must be contiguous int32 tensors")
+    ref = k_layers[0] if nl else None
+    for t in list(k_layers) + list(v_layers):
+        if t.dim() != 3 or t.stride(2) != 1 or t.stride() != ref.stride() or t.dtype != ref.dtype:
+            raise ValueError("every layer's K and V must be [T, Hkv, d] with the same strides and dtype")
+    if ref is not None:
+        desc = AttnDesc(_dtype_code(ref), ref.shape[1], ref.shape[1], ref.shape[2], 0.0,
+                        ref.stride(0), ref.stride(1))
+    else:
+        d0 = hidden_rows
+        desc = AttnDesc(_dtype_code(d0), 1, 1, 64, 0.0, 64, 64)
+    kp = (ctypes.c_void_p * max(nl, 1))(*[t.data_ptr() for t in k_layers])
+    vp_ = (ctypes.c_void_p * max(nl, 1))(*[t.data_ptr() for t in v_layers])
+    H = 0
+    if hidden_rows is not None:
+        if not hidden_rows.is_contiguous():
+            raise ValueError("hidden_rows must be contiguous")
+        H = hidden_rows.shape[1]
+        if next_hidden is None:
+            next_hidden = torch.empty((B, H), dtype=hidden_rows.dtype, device=hidden_rows.device)
+    _check(lib.sparrow_kv_commit(ctypes.byref(desc), kp, vp_, nl, _i32p(cu), B, n_q,
+                                 _ptr(accept_path), _ptr(accept_len), _ptr(hidden_rows), H,
+                                 _ptr(next_hidden), _stream_ptr(stream)))
+    return next_hidden

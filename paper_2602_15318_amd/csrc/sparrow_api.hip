@@ -11,6 +11,7 @@
 #include "accept.hpp"
 #include "draft_window_attn.hpp"
 #include "hsr_input.hpp"
+#include "kv_commit.hpp"
 #include "verify_attn.hpp"
 
 namespace sparrow {
@@ -176,6 +177,55 @@ int sparrow_draft_qkv_append(const sparrow_attn_desc *desc, const void *z, const
   a.Hq = desc->n_q_heads; a.Hkv = desc->n_kv_heads; a.d = desc->head_dim;
   const hipError_t e = launch_draft_qkv(desc->dtype, a, (hipStream_t)hip_stream);
   if (e != hipSuccess) return fail(SPARROW_ERR_DEVICE, "draft_qkv launch: %s", hipGetErrorString(e));
+  return SPARROW_OK;
+}
+
+// ------------------------------------------------------------------ post-accept commit
+int sparrow_kv_commit(const sparrow_attn_desc *desc, void *const *k_layers, void *const *v_layers,
+                      int32_t n_layers, const int32_t *cu_seqlens, int32_t B, int32_t n_q,
+                      const int32_t *accept_path, const int32_t *accept_len,
+                      const void *hidden_rows, int32_t hidden, void *next_hidden,
+                      void *hip_stream) {
+  g_err[0] = 0;
+  if (int rc = check_desc(desc)) return rc;
+  if (n_layers < 0 || B < 0 || n_q < 0)
+    return fail(SPARROW_ERR_INVALID_ARG, "n_layers = %d, B = %d, n_q = %d: negative", n_layers, B, n_q);
+  if (n_layers > kCommitMaxLayers) return fail(SPARROW_ERR_UNSUPPORTED, "n_layers = %d exceeds %d", n_layers, kCommitMaxLayers);
+  if (B > SPARROW_MAX_BATCH) return fail(SPARROW_ERR_UNSUPPORTED, "B = %d exceeds %d", B, SPARROW_MAX_BATCH);
+  if (n_q > SPARROW_MAX_NQ) return fail(SPARROW_ERR_UNSUPPORTED, "n_q = %d exceeds %d", n_q, SPARROW_MAX_NQ);
+  if (B == 0 || (n_layers == 0 && !hidden_rows)) return SPARROW_OK;
+  if (!cu_seqlens || !accept_path || !accept_len)
+    return fail(SPARROW_ERR_INVALID_ARG, "NULL pointer among cu_seqlens/accept_path/accept_len");
+  if (n_layers > 0 && (!k_layers || !v_layers)) return fail(SPARROW_ERR_INVALID_ARG, "k_layers / v_layers is NULL");
+  const int esize = desc->dtype == SPARROW_BF16 ? 2 : 4;
+  CommitArgs a;
+  memset(&a, 0, sizeof(a));
+  for (int l = 0; l < n_layers; ++l) {
+    if (!k_layers[l] || !v_layers[l] || !aligned16(k_layers[l]) || !aligned16(v_layers[l]))
+      return fail(SPARROW_ERR_INVALID_ARG, "layer %d: K/V pointer NULL or not 16-byte aligned", l);
+    a.k[l] = k_layers[l];
+    a.v[l] = v_layers[l];
+  }
+  if (cu_seqlens[0] < 0) return fail(SPARROW_ERR_INVALID_ARG, "cu_seqlens[0] must be >= 0");
+  for (int b = 0; b < B; ++b)
+    if (cu_seqlens[b + 1] - cu_seqlens[b] < n_q)
+      return fail(SPARROW_ERR_INVALID_ARG, "sequence %d has %d rows, fewer than its n_q = %d draft rows",
+                  b, cu_seqlens[b + 1] - cu_seqlens[b], n_q);
+  for (int b = 0; b <= B; ++b) a.cu_len[b] = cu_seqlens[b];
+  if (hidden_rows) {
+    if (!next_hidden) return fail(SPARROW_ERR_INVALID_ARG, "hidden_rows given but next_hidden is NULL");
+    if (hidden <= 0 || (hidden * esize) % 16 != 0)
+      return fail(SPARROW_ERR_UNSUPPORTED, "hidden = %d: rows must be a positive multiple of 16 bytes", hidden);
+    if (!aligned16(hidden_rows) || !aligned16(next_hidden))
+      return fail(SPARROW_ERR_INVALID_ARG, "hidden_rows and next_hidden must be 16-byte aligned");
+  }
+  a.accept_path = accept_path; a.accept_len = accept_len;
+  a.hidden = hidden_rows; a.next_hidden = next_hidden;
+  a.stride_tok = desc->kv_stride_token; a.stride_head = desc->kv_stride_head;
+  a.n_layers = n_layers; a.B = B; a.n_q = n_q; a.Hkv = desc->n_kv_heads; a.d = desc->head_dim;
+  a.H = hidden; a.esize = esize;
+  const hipError_t e = launch_kv_commit(a, (hipStream_t)hip_stream);
+  if (e != hipSuccess) return fail(SPARROW_ERR_DEVICE, "kv_commit launch: %s", hipGetErrorString(e));
   return SPARROW_OK;
 }
 
