@@ -50,6 +50,7 @@ def _load():
         _lib.oracle_draft_qkv.restype = None
         _lib.oracle_rope_table.restype = None
         _lib.oracle_kv_commit.restype = None
+        _lib.oracle_accept_sample.restype = ctypes.c_int
         _lib.oracle_next_hidden.restype = None
     return _lib
 
@@ -249,3 +250,35 @@ def next_hidden(hidden, B: int, n_q: int, accept_path, accept_len) -> np.ndarray
     lib.oracle_next_hidden(_ptr(h, _dp), ctypes.c_int(B), ctypes.c_int(n_q), ctypes.c_int(H),
                            _ptr(path, _ip), _ptr(alen, _ip), _ptr(out, _dp))
     return out
+
+
+def accept_sample(lg, draft_ids, parent, B: int, n_q: int, temperature: float, u_accept, u_bonus):
+    """Stochastic (temperature > 0) acceptance on given logits [B*(n_q+1), V].  Returns
+    (accept_len [B], accept_path [B, n_q], bonus_id [B], margin [B])."""
+    lib = _load()
+    lg = _f64(lg)
+    V = lg.shape[1]
+    assert lg.shape[0] == B * (n_q + 1)
+    dr = _i32(draft_ids)
+    par = None if parent is None else _i32(parent)
+    ua, ub = _f64(u_accept).reshape(B, max(n_q, 0)), _f64(u_bonus)
+    alen = np.empty(B, dtype=np.int32)
+    path = np.empty((B, n_q), dtype=np.int32)
+    bonus = np.empty(B, dtype=np.int32)
+    margin = np.empty(B, dtype=np.float64)
+    rc = lib.oracle_accept_sample(_ptr(lg, _dp), _ptr(dr, _ip), _ptr(par, _ip), ctypes.c_int(B),
+                                  ctypes.c_int(n_q), ctypes.c_int64(V), ctypes.c_double(temperature),
+                                  _ptr(ua, _dp), _ptr(ub, _dp), _ptr(alen, _ip), _ptr(path, _ip),
+                                  _ptr(bonus, _ip), _ptr(margin, _dp))
+    if rc != 0:
+        raise ValueError(f"oracle_accept_sample: bad arguments ({rc})")
+    return alen, path, bonus, margin
+
+
+def accept_sample_step(hidden, lm_head, draft_ids, parent, B: int, n_q: int, temperature: float,
+                       u_accept, u_bonus):
+    """lm_head GEMM + stochastic acceptance, as one step."""
+    lg = logits(hidden, lm_head)
+    alen, path, bonus, margin = accept_sample(lg, draft_ids, parent, B, n_q, temperature,
+                                              u_accept, u_bonus)
+    return {"accept_len": alen, "accept_path": path, "bonus_id": bonus, "margin": margin}

@@ -348,3 +348,93 @@ void oracle_next_hidden(const double *hidden, int B, int n_q, int H, const int32
         memcpy(out + (int64_t)b * H, hidden + ((int64_t)b * (n_q + 1) + row) * H, sizeof(double) * H);
     }
 }
+
+/* ------------------------------------------------------------------------
+ * Stochastic acceptance (temperature > 0), lossless: the paper reports a
+ * Temp = 1 regime for its dynamic draft trees and relies on the distribution
+ * guarantee of speculative sampling (Related Work, first paragraph) without
+ * restating the rule.  Reading taken: the recursive rejection rule of the
+ * tree-speculation line of work it builds on, for trees whose nodes are chosen
+ * deterministically (top-k), i.e. a draft that proposes each child with
+ * certainty:
+ *   at the current node, p = softmax(logits / T) of the node's row;
+ *   its children are tried in increasing node index; child j with token x
+ *   is accepted if  u_accept[j] * S <= p[x],  where S is the probability mass
+ *   not yet rejected (1 at first); otherwise x is struck out (S -= p[x],
+ *   p[x] = 0) and the next child is tried (a child whose token is already
+ *   struck out is skipped);
+ *   an accepted child becomes the current node; if no child is accepted (or
+ *   the node is a leaf) the step ends with a bonus token drawn from what is
+ *   left of p by inverse CDF in vocabulary order:
+ *   bonus = min { t : sum_{v <= t} p[v] >= u_bonus * S }.
+ * The first token emitted this way is distributed exactly as p.
+ *
+ * logits [B*(n_q+1), V] (row 0 of a sequence = last accepted token, row 1+i =
+ * node i); u_accept [B, n_q], u_bonus [B] uniforms in [0, 1) supplied by the
+ * caller.  Outputs as in oracle_accept.  margin (optional, [B]) = the smallest
+ * distance of any decision of the walk from its threshold, relative to the
+ * threshold's scale: min over tests of |u S - p[x]| / S and, for the bonus, of
+ * the distance of u S to the two CDF values around it divided by S.
+ * ------------------------------------------------------------------------ */
+int oracle_accept_sample(const double *logits, const int32_t *draft_ids, const int32_t *parent,
+                         int B, int n_q, int64_t V, double temperature, const double *u_accept,
+                         const double *u_bonus, int32_t *accept_len, int32_t *accept_path,
+                         int32_t *bonus_id, double *margin)
+{
+    if (!(temperature > 0.0)) return -2;
+    for (int i = 0; parent && i < n_q; ++i)
+        if (parent[i] < -1 || parent[i] >= i) return -1;
+    double *p = (double *)malloc(sizeof(double) * (size_t)V);
+    for (int b = 0; b < B; ++b) {
+        const int32_t *dr = draft_ids + (int64_t)b * n_q;
+        int32_t *path = accept_path + (int64_t)b * n_q;
+        for (int i = 0; i < n_q; ++i) path[i] = -1;
+        int cur = -1, len = 0;
+        double worst = INFINITY;
+        for (;;) {
+            const double *lr = logits + ((int64_t)b * (n_q + 1) + cur + 1) * V;
+            double mx = -INFINITY, Z = 0.0;
+            for (int64_t v = 0; v < V; ++v) if (lr[v] / temperature > mx) mx = lr[v] / temperature;
+            for (int64_t v = 0; v < V; ++v) { p[v] = exp(lr[v] / temperature - mx); Z += p[v]; }
+            for (int64_t v = 0; v < V; ++v) p[v] /= Z;
+            double S = 1.0;
+            int next = -1;
+            for (int j = 0; j < n_q && next < 0; ++j) {
+                const int pj = parent ? parent[j] : j - 1;
+                if (pj != cur) continue;
+                const int32_t x = dr[j];
+                if (x < 0 || x >= V || p[x] == 0.0) continue;      /* struck out already */
+                const double lhs = u_accept[(int64_t)b * n_q + j] * S;
+                const double gap = fabs(lhs - p[x]) / S;
+                if (gap < worst) worst = gap;
+                if (lhs <= p[x]) next = j;
+                else { S -= p[x]; p[x] = 0.0; }
+            }
+            if (next >= 0) { path[len++] = next; cur = next; continue; }
+            /* bonus token from the remaining mass */
+            const double target = u_bonus[b] * S;
+            double cdf = 0.0;
+            int64_t pick = -1, last_pos = -1;
+            for (int64_t v = 0; v < V; ++v) {
+                if (p[v] <= 0.0) continue;
+                last_pos = v;
+                const double before = cdf;
+                cdf += p[v];
+                if (cdf >= target) {
+                    pick = v;
+                    double g = (cdf - target) / S;
+                    if (before > 0.0 && (target - before) / S < g) g = (target - before) / S;
+                    if (g < worst) worst = g;
+                    break;
+                }
+            }
+            if (pick < 0) pick = last_pos;          /* rounding left the sum a hair below target */
+            bonus_id[b] = (int32_t)pick;
+            break;
+        }
+        accept_len[b] = len;
+        if (margin) margin[b] = worst;
+    }
+    free(p);
+    return 0;
+}
