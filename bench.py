@@ -170,8 +170,21 @@ def main() -> int:
     def commit_many():
         for _ in range(10):
             sp.kv_commit(ks_all, vs_all, cu, n_q, c_path, c_len, hidden_rows=hidden, next_hidden=c_next)
+    # acceptance at temperature 1 (the paper's second regime; not part of `value`): lm_head with
+    # stored logits, row statistics, tree walk with rejection and bonus draw
+    ws_s = torch.empty(sp.accept_sample_workspace_bytes(1, 1, n_q, cfg.hidden, cfg.vocab),
+                       dtype=torch.uint8, device="cuda")
+    s_ua = torch.rand(1, n_q, device="cuda")
+    s_ub = torch.rand(1, device="cuda")
+    s_out = {"accept_len": a_out["accept_len"].clone(), "accept_path": a_out["accept_path"].clone(),
+             "bonus_id": a_out["bonus_id"].clone()}
+    def accept_sample():
+        sp.accept_sample(hidden, lm_head, draft_ids, None, 1, n_q, 1.0, s_ua, s_ub, workspace=ws_s,
+                         outputs=s_out)
     if args.profile_only:
         fc_many(); qkv_many(); commit_many()    # the kernels around the step, for the trace
+        for _ in range(5):
+            accept_sample()
         torch.cuda.synchronize()
         # calibration for the HBM-traffic counters: a plain copy kernel of known size
         # (1 GiB read + 1 GiB written per launch) in the same profile
@@ -202,6 +215,7 @@ def main() -> int:
             draft()
     us_draft = time_graph(capture(draft_many), 20) / 28
     us_accept = time_graph(capture(accept), 20)
+    us_accept_sample = time_graph(capture(accept_sample), 20)
 
     us_fc = time_graph(capture(fc_many), 20) / (2 * n_copies)
     us_qkv = time_graph(capture(qkv_many), 20) / (2 * n_copies)
@@ -255,6 +269,7 @@ def main() -> int:
                         "draft_qkv_append_us": round(us_qkv, 2),
                         "draft_qkv_append_gbps": round(bytes_qkv / us_qkv * 1e-3, 1)},
         "kv_commit_us": round(us_commit, 2),
+        "accept_sample_t1_us": round(us_accept_sample, 2),
         "roofline": {"bound": "hbm", "kernel": "verify_partial_mfma_kernel (split-context partial "
                                                "pass of verify attention, one layer per launch)",
                      "achieved": round(gbps_partial, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",

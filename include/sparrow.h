@@ -5,6 +5,7 @@
  *   sparrow_draft_window_attn   draft model's text-anchored window attention
  *   sparrow_verify_attn         target model's verification attention
  *   sparrow_accept              lm_head GEMM -> per-row argmax -> greedy acceptance
+ *   sparrow_accept_sample       the same at temperature > 0 (rejection rule + bonus draw)
  * and, one step upstream of the draft attention,
  *   sparrow_hsr_fc              draft input by hidden state reuse
  *   sparrow_draft_qkv_append    draft layer norm / QKV / rotary step + K/V append
@@ -167,6 +168,42 @@ int sparrow_accept(int32_t dtype, const void *hidden_rows, const void *lm_head,
                    int32_t hidden, int32_t vocab, int32_t *target_ids, int32_t *accept_len,
                    int32_t *accept_path, int32_t *bonus_id, void *workspace,
                    size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Stochastic acceptance at temperature > 0, lossless (the paper's "Temp = 1"
+ * regime; it relies on the distribution guarantee of speculative sampling,
+ * Related Work, and does not restate the rule).  Rule implemented: recursive
+ * rejection over the children of the current tree node, for draft trees whose
+ * nodes are chosen deterministically (dynamic top-k trees, Experiment
+ * section), i.e. a draft that proposes each child with certainty.  With
+ * p = softmax(logits / temperature) of the current node's row and S = 1:
+ * children are tried in increasing node index; child j with token x is
+ * accepted if u_accept[b][j] * S <= p[x]; otherwise x is struck out (S -= p[x],
+ * p[x] = 0; a later child with a struck-out token is skipped).  The accepted
+ * child becomes the current node.  When no child is accepted, or at a leaf,
+ * the bonus token is drawn from what is left of p by inverse CDF in
+ * vocabulary order: bonus = min { t : sum_{v<=t} p[v] >= u_bonus[b] * S }.
+ * The first token emitted by a step is then distributed exactly as p.
+ *
+ *  Arguments as sparrow_accept (logits = hidden_rows . lm_head^T), plus
+ *  temperature > 0
+ *  u_accept    dev float [B, n_q]   uniforms in [0, 1) supplied by the caller, one per node
+ *  u_bonus     dev float [B]
+ *  accept_len, accept_path, bonus_id   as sparrow_accept (no target_ids: there is no single
+ *                                       target token per row)
+ *  workspace   dev, at least sparrow_accept_sample_workspace() bytes, 256-byte aligned (argmax
+ *              candidates, the B*(n_q+1) x vocab fp32 logits, per-row softmax statistics)
+ *  All arithmetic of the rule is fp32 (exp2 of pre-scaled logits); a decision closer to its
+ *  threshold than ~1e-5 of the row's mass may differ from exact arithmetic.
+ */
+size_t sparrow_accept_sample_workspace(int32_t dtype, int32_t B, int32_t n_q, int32_t hidden,
+                                       int32_t vocab);
+int sparrow_accept_sample(int32_t dtype, const void *hidden_rows, const void *lm_head,
+                          const int32_t *draft_ids, const int32_t *parent, int32_t B, int32_t n_q,
+                          int32_t hidden, int32_t vocab, float temperature, const float *u_accept,
+                          const float *u_bonus, int32_t *accept_len, int32_t *accept_path,
+                          int32_t *bonus_id, void *workspace, size_t workspace_bytes,
+                          void *hip_stream);
 
 /*
  * Input of the draft model by hidden state reuse (Section "Visually-Aware

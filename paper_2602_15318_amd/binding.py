@@ -71,6 +71,12 @@ def _load() -> ctypes.CDLL:
     L.sparrow_kv_commit.argtypes = [dp, ctypes.POINTER(ctypes.c_void_p), ctypes.POINTER(ctypes.c_void_p),
                                     ctypes.c_int32, i32p, ctypes.c_int32, ctypes.c_int32, vp, vp,
                                     vp, ctypes.c_int32, vp, vp]
+    L.sparrow_accept_sample_workspace.restype = ctypes.c_size_t
+    L.sparrow_accept_sample_workspace.argtypes = [ctypes.c_int32] * 5
+    L.sparrow_accept_sample.restype = ctypes.c_int
+    L.sparrow_accept_sample.argtypes = [ctypes.c_int32, vp, vp, vp, vp, ctypes.c_int32, ctypes.c_int32,
+                                        ctypes.c_int32, ctypes.c_int32, ctypes.c_float, vp, vp,
+                                        vp, vp, vp, vp, ctypes.c_size_t, vp]
     return L
 
 
@@ -304,3 +310,36 @@ def kv_commit(k_layers, v_layers, cu_seqlens, n_q: int, accept_path, accept_len,
                                  _ptr(accept_path), _ptr(accept_len), _ptr(hidden_rows), H,
                                  _ptr(next_hidden), _stream_ptr(stream)))
     return next_hidden
+
+
+def accept_sample_workspace_bytes(dtype_code: int, B: int, n_q: int, hidden: int, vocab: int) -> int:
+    return int(lib.sparrow_accept_sample_workspace(dtype_code, B, n_q, hidden, vocab))
+
+
+def accept_sample(hidden_rows, lm_head, draft_ids, parent, B: int, n_q: int, temperature: float,
+                  u_accept, u_bonus, workspace=None, outputs=None, stream=None):
+    """sparrow_accept_sample.  u_accept float32 [B,n_q], u_bonus float32 [B] device tensors.
+    Returns {"accept_len", "accept_path", "bonus_id"} (int32 device tensors)."""
+    M, H = hidden_rows.shape
+    V = lm_head.shape[0]
+    if M != B * (n_q + 1) or lm_head.shape[1] != H:
+        raise ValueError("hidden_rows must be [B*(n_q+1), H] and lm_head [V, H]")
+    if not hidden_rows.is_contiguous() or not lm_head.is_contiguous() or lm_head.dtype != hidden_rows.dtype:
+        raise ValueError("hidden_rows and lm_head must be contiguous and of one dtype")
+    for t in (u_accept, u_bonus):
+        if t.dtype != torch.float32 or not t.is_contiguous():
+            raise ValueError("u_accept and u_bonus must be contiguous float32 tensors")
+    dev = hidden_rows.device
+    code = _dtype_code(hidden_rows)
+    ws = _workspace(accept_sample_workspace_bytes(code, B, n_q, H, V), dev, workspace)
+    if outputs is None:
+        outputs = {"accept_len": torch.empty(B, dtype=torch.int32, device=dev),
+                   "accept_path": torch.empty((B, n_q), dtype=torch.int32, device=dev),
+                   "bonus_id": torch.empty(B, dtype=torch.int32, device=dev)}
+    _check(lib.sparrow_accept_sample(code, _ptr(hidden_rows), _ptr(lm_head), _ptr(draft_ids),
+                                     _ptr(parent), B, n_q, H, V, float(temperature),
+                                     _ptr(u_accept), _ptr(u_bonus), _ptr(outputs["accept_len"]),
+                                     _ptr(outputs["accept_path"]) if n_q > 0 else None,
+                                     _ptr(outputs["bonus_id"]), _ptr(ws),
+                                     0 if ws is None else ws.numel(), _stream_ptr(stream)))
+    return outputs

@@ -65,6 +65,8 @@ __global__ void __launch_bounds__(256) lm_head_generic_kernel(AcceptArgs a) {
         for (int r = 0; r < kGenMC; ++r) {
           const float s = wave_sum(acc[j][r]);
           if (v < v1 && s > best[r]) { best[r] = s; best_i[r] = v; }   // ascending v: lowest wins
+          if (a.logits != nullptr && lane == 0 && v < v1 && r0 + r < a.M)
+            a.logits[(int64_t)(r0 + r) * a.V + v] = s;
         }
       }
     }

@@ -19,7 +19,27 @@ struct AcceptArgs {
   float *cand_val;           // [M, n_cand]
   int32_t *cand_idx;         // [M, n_cand]
   int32_t *target_ids, *accept_len, *accept_path, *bonus_id;
+  float *logits;             // [M, V] or nullptr: the GEMM pass also stores every logit (sampling)
 };
+
+// Stochastic acceptance (temperature > 0) on stored logits.
+constexpr int kStatChunks = 64;   // partial (max, sum of exponentials) per row
+constexpr int kSampleMaxVocab = 1 << 20;   // the bonus draw keeps one fp64 sum per 256 tokens in LDS
+struct SampleArgs {
+  const float *logits;       // [M, V]
+  const int32_t *draft_ids;  // [B*n_q]
+  const int32_t *parent;     // [n_q] or nullptr
+  const float *u_accept;     // [B, n_q]
+  const float *u_bonus;      // [B]
+  float *stats;              // [M, kStatChunks, 2]: max and sum of exponentials per chunk
+  float *blk_sum;            // [M, ceil(V / 256)]: sum of exponentials per block, relative to the
+                             // max of the block's chunk (chunk = ceil(blocks / 64) blocks)
+  int32_t *accept_len, *accept_path, *bonus_id;
+  int32_t B, n_q, M, V;
+  float inv_temp_log2;       // log2(e) / temperature
+};
+hipError_t launch_logit_stats(const SampleArgs &a, hipStream_t st);
+hipError_t launch_accept_sample(const SampleArgs &a, hipStream_t st);
 
 // Number of per-row argmax candidates the GEMM pass writes (one per wavefront / tile owner).
 int accept_num_candidates(int dtype, int M, int H, int V);

@@ -96,6 +96,8 @@ lm_head_mfma_kernel(AcceptArgs a, int row0) {
       for (int i = 0; i < 4; ++i) {
         const float lg = acc0[i] + acc1[i];
         if (vbase + i < V && lg > best) { best = lg; best_i = vbase + i; }   // ascending: lowest wins
+        if (a.logits != nullptr && vbase + i < V && row0 + n < a.M)
+          a.logits[(int64_t)(row0 + n) * V + vbase + i] = lg;
       }
       acc0 = (f32x4){0.f, 0.f, 0.f, 0.f};
       acc1 = (f32x4){0.f, 0.f, 0.f, 0.f};
@@ -242,6 +244,12 @@ lm_head_ksplit_kernel(AcceptArgs a, int row0) {
 #pragma unroll
           for (int i = 0; i < 4; ++i)
             if (vbase + i < V && sum[i] > best[nb]) { best[nb] = sum[i]; best_i[nb] = vbase + i; }
+          if (a.logits != nullptr) {
+            const int row = row0 + 16 * nb + n;
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+              if (vbase + i < V && row < a.M) a.logits[(int64_t)row * V + vbase + i] = sum[i];
+          }
         }
         __syncthreads();   // reads done before the next partials are written
       }

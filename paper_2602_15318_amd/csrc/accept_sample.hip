@@ -1,0 +1,271 @@
+// Stochastic (temperature > 0) tree acceptance on the logits stored by the lm_head pass.
+//
+//   logit_stats_kernel   the whole chip reads the M x V logits once (grid M x 64 chunks): per
+//                        chunk the max and the sum of exponentials of logits / T, and per block of
+//                        256 tokens the sum of exponentials relative to the chunk's max;
+//   accept_sample_kernel one workgroup per sequence walks the tree: at the current node it merges
+//                        the row's 64 chunk statistics, evaluates the children's probabilities
+//                        in parallel, lets one thread apply the sequential rejection rule
+//                        (u * S <= p[x] accepts; a rejected token is struck out and its mass leaves
+//                        S), and, when no child is accepted, draws the bonus token from what is
+//                        left by inverse CDF in vocabulary order: a scan over the row's block
+//                        sums (struck-out tokens taken out), then a search inside the one block
+//                        that holds the target -- the only 256 logits of the row it reads.
+// Exponentials are exp2 of logits pre-multiplied by log2(e) / T in fp32; sums across blocks fp64.
+#include "accept.hpp"
+#include "common.hpp"
+
+namespace sparrow {
+
+namespace {
+
+constexpr int kStatThreads = 256;
+constexpr int kWalkThreads = 1024;
+constexpr int kBonusBlock = 256;              // tokens per block of the bonus draw
+constexpr int kBonusMaxBlocks = kSampleMaxVocab / kBonusBlock;
+
+__global__ void __launch_bounds__(kStatThreads)
+logit_stats_kernel(SampleArgs a) {
+  __shared__ float red[kStatThreads / 64];
+  const int c = blockIdx.x, r = blockIdx.y;
+  const int n_blk = (a.V + kBonusBlock - 1) / kBonusBlock;
+  const int bpc = (n_blk + kStatChunks - 1) / kStatChunks;          // blocks per chunk
+  const int b0 = min(n_blk, c * bpc), b1 = min(n_blk, b0 + bpc);
+  const int v0 = b0 * kBonusBlock, v1 = min(a.V, b1 * kBonusBlock);
+  const float *lg = a.logits + (int64_t)r * a.V;
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  float m = kNegBig;
+  for (int v = v0 + threadIdx.x; v < v1; v += kStatThreads) m = fmaxf(m, lg[v] * a.inv_temp_log2);
+  m = wave_max(m);
+  if (lane == 0) red[w] = m;
+  __syncthreads();
+  m = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+  __syncthreads();
+  // block sums relative to the chunk's max (a wavefront per block, a lane reads 4 tokens)
+  float s = 0.f;
+  for (int ib = b0 + w; ib < b1; ib += kStatThreads / 64) {
+    const int v = ib * kBonusBlock + 4 * lane;
+    float t = 0.f;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      if (v + i < a.V) t += fast_exp2(lg[v + i] * a.inv_temp_log2 - m);
+    t = wave_sum_valu(t);
+    if (lane == 0) a.blk_sum[(int64_t)r * n_blk + ib] = t;
+    s += t;                                   // the same value in every lane
+  }
+  if (lane == 0) red[w] = s;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    float *o = a.stats + ((int64_t)r * kStatChunks + c) * 2;
+    o[0] = m;                                   // kNegBig and sum 0 for an empty chunk
+    o[1] = red[0] + red[1] + red[2] + red[3];
+  }
+}
+
+__global__ void __launch_bounds__(kWalkThreads)
+accept_sample_kernel(SampleArgs a) {
+  __shared__ float cand_p[SPARROW_MAX_NQ];      // probability of child j's token, -1 if not a child
+  __shared__ float cand_u[SPARROW_MAX_NQ];      // the uniform that decides child j
+  __shared__ int struck[SPARROW_MAX_NQ];        // tokens rejected at the current node
+  __shared__ int sh_next, sh_nstruck;
+  __shared__ float sh_S, sh_m, sh_Z;
+  __shared__ double wave_tot[kWalkThreads / 64];
+  __shared__ int sh_owner, sh_last, sh_pick, sh_blk;
+  __shared__ double sh_excl;
+  __shared__ double blk_tot[kBonusMaxBlocks];   // sum of the live exponentials of 256 tokens
+  __shared__ float chunk_m[kStatChunks];        // max of every chunk of the current row
+  const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const int n_q = a.n_q, V = a.V;
+  const int32_t *dr = a.draft_ids + (int64_t)b * n_q;
+  int32_t *path = a.accept_path + (int64_t)b * n_q;
+  for (int i = tid; i < n_q; i += kWalkThreads) path[i] = -1;
+  int cur = -1, len = 0;
+  // at most n_q + 1 levels: cur strictly increases along a path
+  for (int level = 0; level <= n_q; ++level) {
+    const int64_t row = (int64_t)b * (n_q + 1) + cur + 1;
+    const float *lg = a.logits + row * V;
+    // ---- row statistics from the 64 chunk partials (wavefront 0)
+    if (w == 0) {
+      const float pm = a.stats[(row * kStatChunks + lane) * 2];
+      const float ps = a.stats[(row * kStatChunks + lane) * 2 + 1];
+      const float m = wave_max(pm);
+      const float Z = wave_sum(ps * fast_exp2(pm - m));
+      chunk_m[lane] = pm;
+      if (lane == 0) { sh_m = m; sh_Z = Z; }
+    }
+    __syncthreads();
+    const float m = sh_m, Z = sh_Z;
+    // ---- children of cur and the probabilities of their tokens
+    if (tid < n_q) {
+      const int pj = a.parent ? a.parent[tid] : tid - 1;
+      const int x = dr[tid];
+      float p = -1.f;
+      if (pj == cur && x >= 0 && x < V) p = fast_exp2(lg[x] * a.inv_temp_log2 - m) / Z;
+      cand_p[tid] = p;
+      cand_u[tid] = a.u_accept[(int64_t)b * n_q + tid];
+    }
+    __syncthreads();
+    if (tid == 0) {
+      float S = 1.f;
+      int next = -1, ns = 0;
+      for (int j = 0; j < n_q && next < 0; ++j) {
+        const float p = cand_p[j];
+        if (p < 0.f) continue;
+        const int x = dr[j];
+        bool gone = false;
+        for (int k = 0; k < ns; ++k) gone |= struck[k] == x;
+        if (gone || p == 0.f) continue;
+        if (cand_u[j] * S <= p) next = j;
+        else { S -= p; struck[ns++] = x; }
+      }
+      sh_next = next; sh_S = S; sh_nstruck = ns;
+      sh_owner = kWalkThreads; sh_last = -1; sh_pick = -1;
+    }
+    __syncthreads();
+    const int next = sh_next;
+    if (next >= 0) {
+      if (tid == 0) path[len] = next;
+      ++len;
+      cur = next;
+      __syncthreads();          // cand_p / struck are rewritten at the next level
+      continue;
+    }
+    // ---- bonus token: inverse CDF over what is left of the row's distribution.  The sums of
+    // the row's 256-token blocks come from the statistics pass (relative to their chunk's max);
+    // rescaled to the row's max, minus the struck-out tokens, they are scanned in fp64 (fp32
+    // inside a block, whose sum is a small part of the mass), so the draw is decided by the fp32
+    // exponentials alone (~1e-7 of the remaining mass).  Only the block that holds the target
+    // is read from the logits.
+    const int ns = sh_nstruck;
+    const double target = (double)a.u_bonus[b] * (double)sh_S * (double)Z;   // unnormalised units
+    auto weight = [&](int v) {
+      bool gone = false;
+      for (int k = 0; k < ns; ++k) gone |= struck[k] == v;
+      return gone ? 0.f : fast_exp2(lg[v] * a.inv_temp_log2 - m);
+    };
+    // the 4 weights of this lane in block ib (0 past the end of the vocabulary)
+    auto lane_weights = [&](int ib, float *e) {
+      const int v = ib * kBonusBlock + 4 * lane;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) e[i] = (v + i < V) ? weight(v + i) : 0.f;
+    };
+    const int n_blk = (V + kBonusBlock - 1) / kBonusBlock;
+    const int bpc = (n_blk + kStatChunks - 1) / kStatChunks;
+    const float *bs = a.blk_sum + row * n_blk;
+    for (int ib = tid; ib < n_blk; ib += kWalkThreads)
+      blk_tot[ib] = (double)bs[ib] * (double)fast_exp2(chunk_m[ib / bpc] - m);
+    __syncthreads();
+    if (tid == 0) {                  // struck-out tokens leave their blocks
+      for (int k = 0; k < ns; ++k) {
+        const int x = struck[k];
+        const double left = blk_tot[x / kBonusBlock] - (double)fast_exp2(lg[x] * a.inv_temp_log2 - m);
+        blk_tot[x / kBonusBlock] = left > 0.0 ? left : 0.0;
+      }
+    }
+    __syncthreads();
+    // scan over the block sums: thread t owns blocks [t*bp, (t+1)*bp)
+    const int bp = (n_blk + kWalkThreads - 1) / kWalkThreads;
+    double local = 0.0;
+    int last_blk = -1;
+    for (int i = 0; i < bp; ++i) {
+      const int ib = tid * bp + i;
+      if (ib < n_blk) {
+        local += blk_tot[ib];
+        if (blk_tot[ib] > 0.0) last_blk = ib;
+      }
+    }
+    if (last_blk >= 0) atomicMax(&sh_last, last_blk);      // last live block of the row
+    double incl = local;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      const double up = __shfl_up(incl, o, 64);
+      if (lane >= o) incl += up;
+    }
+    if (lane == 63) wave_tot[w] = incl;
+    __syncthreads();
+    double base = 0.0;
+    for (int k = 0; k < w; ++k) base += wave_tot[k];
+    incl += base;
+    if (local > 0.0 && incl >= target) atomicMin(&sh_owner, tid);
+    __syncthreads();
+    if (tid == sh_owner) {           // which of this thread's blocks holds the target
+      double run = incl - local;
+      int blk = -1;
+      for (int i = 0; i < bp && blk < 0; ++i) {
+        const int ib = tid * bp + i;
+        if (ib < n_blk && blk_tot[ib] > 0.0) {
+          if (run + blk_tot[ib] >= target) blk = ib; else run += blk_tot[ib];
+        }
+      }
+      if (blk < 0) {                 // rounding between the two summation orders: last live block
+        for (int i = bp - 1; i >= 0 && blk < 0; --i) {
+          const int ib = tid * bp + i;
+          if (ib < n_blk && blk_tot[ib] > 0.0) blk = ib;
+        }
+        run = -1.0e300;              // nothing in blk reaches the target: its last live token
+      }
+      sh_blk = blk;
+      sh_excl = run;
+    }
+    __syncthreads();
+    if (w == 0 && (sh_owner < kWalkThreads || sh_last >= 0)) {
+      // the block that holds the target; if rounding left the row's total a hair below the
+      // target, the last live block with nothing to find: its last live token is taken
+      const bool owned = sh_owner < kWalkThreads;
+      const int ib = owned ? sh_blk : sh_last;
+      const double excl0 = owned ? sh_excl : -1.0e300;
+      float e[4];
+      lane_weights(ib, e);
+      const float mine = (e[0] + e[1]) + (e[2] + e[3]);
+      float li = mine;
+#pragma unroll
+      for (int o = 1; o < 64; o <<= 1) {
+        const float up = __shfl_up(li, o, 64);
+        if (lane >= o) li += up;
+      }
+      double run = excl0 + (double)(li - mine);
+      int found = -1, lastp = -1;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        if (e[i] > 0.f) {
+          lastp = ib * kBonusBlock + 4 * lane + i;
+          run += (double)e[i];
+          if (found < 0 && run >= target) found = lastp;
+        }
+      }
+      // first lane that found its element wins (vocabulary order = lane order)
+      const unsigned long long hit = __builtin_amdgcn_ballot_w64(found >= 0);
+      int pick;
+      if (hit != 0ull) {
+        pick = __shfl(found, __builtin_ctzll(hit), 64);
+      } else {                       // a hair below the target after rounding: last live token
+        pick = lastp;
+#pragma unroll
+        for (int o = 32; o >= 1; o >>= 1) pick = max(pick, __shfl_xor(pick, o, 64));
+      }
+      if (lane == 0) sh_pick = pick;
+    }
+    __syncthreads();
+    if (tid == 0) {
+      a.bonus_id[b] = max(sh_pick, 0);
+      a.accept_len[b] = len;
+    }
+    return;
+  }
+  // only reachable with a malformed tree (the walk did not end within n_q + 1 levels)
+  if (tid == 0) { a.accept_len[b] = len; a.bonus_id[b] = 0; }
+}
+
+}  // namespace
+
+hipError_t launch_logit_stats(const SampleArgs &a, hipStream_t st) {
+  hipLaunchKernelGGL(logit_stats_kernel, dim3(kStatChunks, a.M), dim3(kStatThreads), 0, st, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_accept_sample(const SampleArgs &a, hipStream_t st) {
+  hipLaunchKernelGGL(accept_sample_kernel, dim3(a.B), dim3(kWalkThreads), 0, st, a);
+  return hipGetLastError();
+}
+
+}  // namespace sparrow

@@ -97,6 +97,12 @@ template <int N> __device__ __forceinline__ float group_sum(float v) {
   }
   return v;
 }
+// Sum over the whole wavefront on the vector ALU (every lane gets the result).
+__device__ __forceinline__ float wave_sum_valu(float v) {
+  v = group_sum<32>(v);
+  auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
 // Value of lane (lane ^ O) for O = 8, 16 or 32.
 template <int O> __device__ __forceinline__ float lane_xor(float v, int lane) {
   static_assert(O == 8 || O == 16 || O == 32, "supported distances");

@@ -398,11 +398,31 @@ size_t sparrow_accept_workspace(int32_t dtype, int32_t B, int32_t n_q, int32_t h
   return round_up(n * sizeof(float), 256) + round_up(n * sizeof(int32_t), 256);
 }
 
-int sparrow_accept(int32_t dtype, const void *hidden_rows, const void *lm_head,
-                   const int32_t *draft_ids, const int32_t *parent, int32_t B, int32_t n_q,
-                   int32_t hidden, int32_t vocab, int32_t *target_ids, int32_t *accept_len,
-                   int32_t *accept_path, int32_t *bonus_id, void *workspace,
-                   size_t workspace_bytes, void *hip_stream) {
+// Shared body of the greedy and the stochastic acceptance.  sample == nullptr: greedy.
+struct SampleParams {
+  float temperature;
+  const float *u_accept, *u_bonus;
+};
+
+static size_t accept_sample_extra(int M, int vocab, size_t *logits_bytes, size_t *stats_bytes) {
+  *logits_bytes = round_up((size_t)M * vocab * sizeof(float), 256);
+  *stats_bytes = round_up((size_t)M * kStatChunks * 2 * sizeof(float), 256);
+  return *logits_bytes + *stats_bytes + round_up((size_t)M * ((vocab + 255) / 256) * sizeof(float), 256);
+}
+
+size_t sparrow_accept_sample_workspace(int32_t dtype, int32_t B, int32_t n_q, int32_t hidden,
+                                       int32_t vocab) {
+  if (B <= 0 || n_q < 0 || hidden <= 0 || vocab <= 0) return 0;
+  size_t lb, sb;
+  return sparrow_accept_workspace(dtype, B, n_q, hidden, vocab) +
+         accept_sample_extra(B * (n_q + 1), vocab, &lb, &sb);
+}
+
+static int accept_body(int32_t dtype, const void *hidden_rows, const void *lm_head,
+                       const int32_t *draft_ids, const int32_t *parent, int32_t B, int32_t n_q,
+                       int32_t hidden, int32_t vocab, int32_t *target_ids, int32_t *accept_len,
+                       int32_t *accept_path, int32_t *bonus_id, void *workspace,
+                       size_t workspace_bytes, void *hip_stream, const SampleParams *sample) {
   g_err[0] = 0;
   if (dtype != SPARROW_F32 && dtype != SPARROW_BF16)
     return fail(SPARROW_ERR_UNSUPPORTED, "dtype %d is neither SPARROW_F32 nor SPARROW_BF16", dtype);
@@ -415,15 +435,25 @@ int sparrow_accept(int32_t dtype, const void *hidden_rows, const void *lm_head,
   const int per = dtype == SPARROW_BF16 ? 8 : 4;
   if (hidden % per != 0)
     return fail(SPARROW_ERR_UNSUPPORTED, "hidden = %d must be a multiple of %d (16-byte rows)", hidden, per);
-  if (!hidden_rows || !lm_head || !target_ids || !accept_len || !bonus_id ||
+  if (!hidden_rows || !lm_head || (!sample && !target_ids) || !accept_len || !bonus_id ||
       (n_q > 0 && (!draft_ids || !accept_path)))
     return fail(SPARROW_ERR_INVALID_ARG, "NULL pointer among hidden_rows/lm_head/draft_ids/outputs");
+  if (sample) {
+    if (!(sample->temperature > 0.f) || std::isinf(sample->temperature))
+      return fail(SPARROW_ERR_INVALID_ARG, "temperature must be finite and > 0");
+    if (vocab > kSampleMaxVocab)
+      return fail(SPARROW_ERR_UNSUPPORTED, "vocab = %d exceeds %d (stochastic acceptance)", vocab, kSampleMaxVocab);
+    if (!sample->u_bonus || (n_q > 0 && !sample->u_accept))
+      return fail(SPARROW_ERR_INVALID_ARG, "NULL pointer among u_accept/u_bonus");
+  }
   if (!aligned16(hidden_rows) || !aligned16(lm_head))
     return fail(SPARROW_ERR_INVALID_ARG, "hidden_rows and lm_head must be 16-byte aligned");
   const int M = B * (n_q + 1);
   const bool mfma = lm_head_mfma_supported(dtype, M, hidden, vocab);
   const int n_cand = accept_candidates(dtype, M, hidden, vocab);
-  const size_t need = sparrow_accept_workspace(dtype, B, n_q, hidden, vocab);
+  const size_t base = sparrow_accept_workspace(dtype, B, n_q, hidden, vocab);
+  size_t logits_bytes = 0, stats_bytes = 0;
+  const size_t need = base + (sample ? accept_sample_extra(M, vocab, &logits_bytes, &stats_bytes) : 0);
   if (!workspace || workspace_bytes < need)
     return fail(SPARROW_ERR_WORKSPACE, "workspace of %zu bytes needed, %zu given%s", need,
                 workspace_bytes, workspace ? "" : " (NULL)");
@@ -436,12 +466,50 @@ int sparrow_accept(int32_t dtype, const void *hidden_rows, const void *lm_head,
   a.cand_idx = (int32_t *)((char *)workspace + round_up((size_t)M * n_cand * sizeof(float), 256));
   a.target_ids = target_ids; a.accept_len = accept_len; a.accept_path = accept_path;
   a.bonus_id = bonus_id;
+  a.logits = sample ? (float *)((char *)workspace + base) : nullptr;
   hipStream_t st = (hipStream_t)hip_stream;
   hipError_t e = mfma ? launch_lm_head_mfma(a, st) : launch_lm_head_generic(dtype, a, st);
   if (e != hipSuccess) return fail(SPARROW_ERR_DEVICE, "lm_head launch: %s", hipGetErrorString(e));
-  e = launch_accept_finalize(a, st);
-  if (e != hipSuccess) return fail(SPARROW_ERR_DEVICE, "accept finalize launch: %s", hipGetErrorString(e));
+  if (!sample) {
+    e = launch_accept_finalize(a, st);
+    if (e != hipSuccess) return fail(SPARROW_ERR_DEVICE, "accept finalize launch: %s", hipGetErrorString(e));
+    return SPARROW_OK;
+  }
+  SampleArgs s;
+  s.logits = a.logits; s.draft_ids = draft_ids; s.parent = parent;
+  s.u_accept = sample->u_accept; s.u_bonus = sample->u_bonus;
+  s.stats = (float *)((char *)workspace + base + logits_bytes);
+  s.blk_sum = (float *)((char *)workspace + base + logits_bytes + stats_bytes);
+  s.accept_len = accept_len; s.accept_path = accept_path; s.bonus_id = bonus_id;
+  s.B = B; s.n_q = n_q; s.M = M; s.V = vocab;
+  s.inv_temp_log2 = 1.4426950408889634f / sample->temperature;
+  e = launch_logit_stats(s, st);
+  if (e != hipSuccess) return fail(SPARROW_ERR_DEVICE, "logit statistics launch: %s", hipGetErrorString(e));
+  e = launch_accept_sample(s, st);
+  if (e != hipSuccess) return fail(SPARROW_ERR_DEVICE, "accept sample launch: %s", hipGetErrorString(e));
   return SPARROW_OK;
+}
+
+int sparrow_accept(int32_t dtype, const void *hidden_rows, const void *lm_head,
+                   const int32_t *draft_ids, const int32_t *parent, int32_t B, int32_t n_q,
+                   int32_t hidden, int32_t vocab, int32_t *target_ids, int32_t *accept_len,
+                   int32_t *accept_path, int32_t *bonus_id, void *workspace,
+                   size_t workspace_bytes, void *hip_stream) {
+  return accept_body(dtype, hidden_rows, lm_head, draft_ids, parent, B, n_q, hidden, vocab,
+                     target_ids, accept_len, accept_path, bonus_id, workspace, workspace_bytes,
+                     hip_stream, nullptr);
+}
+
+int sparrow_accept_sample(int32_t dtype, const void *hidden_rows, const void *lm_head,
+                          const int32_t *draft_ids, const int32_t *parent, int32_t B, int32_t n_q,
+                          int32_t hidden, int32_t vocab, float temperature, const float *u_accept,
+                          const float *u_bonus, int32_t *accept_len, int32_t *accept_path,
+                          int32_t *bonus_id, void *workspace, size_t workspace_bytes,
+                          void *hip_stream) {
+  const SampleParams sp_ = {temperature, u_accept, u_bonus};
+  return accept_body(dtype, hidden_rows, lm_head, draft_ids, parent, B, n_q, hidden, vocab,
+                     nullptr, accept_len, accept_path, bonus_id, workspace, workspace_bytes,
+                     hip_stream, &sp_);
 }
 
 }  // extern "C"
