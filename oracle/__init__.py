@@ -51,6 +51,9 @@ def _load():
         _lib.oracle_rope_table.restype = None
         _lib.oracle_kv_commit.restype = None
         _lib.oracle_accept_sample.restype = ctypes.c_int
+        _lib.oracle_topk_logprob.restype = None
+        _lib.oracle_tree_expand.restype = ctypes.c_int
+        _lib.oracle_tree_select.restype = ctypes.c_int
         _lib.oracle_next_hidden.restype = None
     return _lib
 
@@ -282,3 +285,63 @@ def accept_sample_step(hidden, lm_head, draft_ids, parent, B: int, n_q: int, tem
     alen, path, bonus, margin = accept_sample(lg, draft_ids, parent, B, n_q, temperature,
                                               u_accept, u_bonus)
     return {"accept_len": alen, "accept_path": path, "bonus_id": bonus, "margin": margin}
+
+
+def topk_logprob(lg, k: int):
+    """Per row: ids [M,k] of the k largest logits (decreasing, ties to the lower id), their
+    log-softmax values [M,k], and the conditioning margin [M]."""
+    lib = _load()
+    lg = _f64(lg)
+    M, V = lg.shape
+    ids = np.empty((M, k), dtype=np.int32)
+    logp = np.empty((M, k), dtype=np.float64)
+    margin = np.empty(M, dtype=np.float64)
+    lib.oracle_topk_logprob(_ptr(lg, _dp), ctypes.c_int(M), ctypes.c_int64(V), ctypes.c_int(k),
+                            _ptr(ids, _ip), _ptr(logp, _dp), _ptr(margin, _dp))
+    return ids, logp, margin
+
+
+class TreePool:
+    """Pool of draft-tree candidates grown level by level (see oracle_tree_expand)."""
+
+    def __init__(self, width: int, depth: int):
+        cap = width + max(depth - 1, 0) * width * width
+        self.width, self.depth = width, depth
+        self.tok = np.zeros(cap, dtype=np.int32)
+        self.par = np.zeros(cap, dtype=np.int32)
+        self.score = np.zeros(cap, dtype=np.float64)
+        self.n = 0
+        self.front = None            # pool indices of the current frontier (None = root)
+        self.margin = np.inf
+
+    def expand(self, cand_ids, cand_logp):
+        lib = _load()
+        ci, cl = _i32(cand_ids), _f64(cand_logp)
+        n_front = 1 if self.front is None else len(self.front)
+        assert ci.shape == (n_front, self.width) and cl.shape == ci.shape
+        fin = None if self.front is None else _i32(self.front)
+        fout = np.empty(self.width, dtype=np.int32)
+        mg = ctypes.c_double(0.0)
+        self.n = lib.oracle_tree_expand(ctypes.c_int(n_front), ctypes.c_int(self.width),
+                                        _ptr(fin, _ip), _ptr(ci, _ip), _ptr(cl, _dp),
+                                        _ptr(self.tok, _ip), _ptr(self.par, _ip),
+                                        _ptr(self.score, _dp), ctypes.c_int(self.n),
+                                        _ptr(fout, _ip), ctypes.byref(mg))
+        self.front = fout
+        self.margin = min(self.margin, mg.value)
+        return fout
+
+    def select(self, total: int):
+        lib = _load()
+        keep = min(total, self.n)
+        parent = np.empty(keep, dtype=np.int32)
+        ids = np.empty(keep, dtype=np.int32)
+        pidx = np.empty(keep, dtype=np.int32)
+        mg = ctypes.c_double(0.0)
+        rc = lib.oracle_tree_select(_ptr(self.tok, _ip), _ptr(self.par, _ip), _ptr(self.score, _dp),
+                                    ctypes.c_int(self.n), ctypes.c_int(total), _ptr(parent, _ip),
+                                    _ptr(ids, _ip), _ptr(pidx, _ip), ctypes.byref(mg))
+        if rc < 0:
+            raise ValueError("kept set is not closed under ancestors")
+        self.margin = min(self.margin, mg.value)
+        return parent, ids, pidx

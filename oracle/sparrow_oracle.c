@@ -438,3 +438,134 @@ int oracle_accept_sample(const double *logits, const int32_t *draft_ids, const i
     free(p);
     return 0;
 }
+
+/* ------------------------------------------------------------------------
+ * Dynamic draft tree (Experiment section: "dynamic tree structure",
+ * configuration total tokens - depth - width, e.g. 30-4-8).  The paper names
+ * the configuration and not the procedure; reading taken: the best-first
+ * expansion of the tree-speculation work it builds on.
+ *   score of a node = sum of the draft's log-probabilities along its path;
+ *   level 0: the `width` most likely tokens after the root;
+ *   level d: every frontier node proposes its `width` most likely next tokens;
+ *            all width*width candidates join the pool, the `width` best of
+ *            them (by score) form the next frontier;
+ *   at the end the `total` best nodes of the whole pool are kept (a node's
+ *   score never exceeds its parent's, so the kept set is closed under
+ *   ancestors), renumbered in pool order (parents before children).
+ * Ties are broken towards the lower pool index / lower token id everywhere.
+ * ------------------------------------------------------------------------ */
+
+/* The k largest logits of every row, in decreasing order (equal values: lower token id first),
+ * with their natural-log softmax values.  margin[r] (optional) = the smallest gap between two
+ * consecutive logits among the k+1 largest of the row (what separates the selected tokens from
+ * each other and from the first one left out). */
+void oracle_topk_logprob(const double *logits, int M, int64_t V, int k, int32_t *ids,
+                         double *logp, double *margin)
+{
+    #pragma omp parallel for schedule(static)
+    for (int r = 0; r < M; ++r) {
+        const double *lr = logits + (int64_t)r * V;
+        double mx = -INFINITY, Z = 0.0;
+        for (int64_t v = 0; v < V; ++v) if (lr[v] > mx) mx = lr[v];
+        for (int64_t v = 0; v < V; ++v) Z += exp(lr[v] - mx);
+        const double lse = mx + log(Z);
+        double prev = INFINITY, worst = INFINITY;
+        int64_t prev_id = -1;
+        for (int j = 0; j <= k; ++j) {           /* selection by repeated scan: k is small */
+            int64_t best = -1;
+            for (int64_t v = 0; v < V; ++v) {
+                const int after_prev = lr[v] < prev || (lr[v] == prev && v > prev_id);
+                if (!after_prev) continue;
+                if (best < 0 || lr[v] > lr[best]) best = v;
+            }
+            if (best < 0) break;
+            if (j > 0 && prev - lr[best] < worst) worst = prev - lr[best];
+            if (j < k) { ids[(int64_t)r * k + j] = (int32_t)best; logp[(int64_t)r * k + j] = lr[best] - lse; }
+            prev = lr[best];
+            prev_id = best;
+        }
+        if (margin) margin[r] = worst;
+    }
+}
+
+/* One level of the expansion.  n_front frontier nodes (pool indices front_in, or NULL at level 0
+ * where the single "frontier node" is the root, index -1, score 0) each propose `width`
+ * candidates (cand_ids, cand_logp [n_front, width]).  The candidates are appended to the pool at
+ * n_pool.. in (frontier order, candidate order); front_out [width] receives the pool indices of
+ * the `width` best of them, best first.  Returns the new pool size.  margin (optional): smallest
+ * score gap between consecutive candidates among the width+1 best. */
+int oracle_tree_expand(int n_front, int width, const int32_t *front_in, const int32_t *cand_ids,
+                       const double *cand_logp, int32_t *pool_tok, int32_t *pool_par,
+                       double *pool_score, int n_pool, int32_t *front_out, double *margin)
+{
+    const int n_new = n_front * width;
+    for (int f = 0; f < n_front; ++f)
+        for (int j = 0; j < width; ++j) {
+            const int p = front_in ? front_in[f] : -1;
+            const int i = n_pool + f * width + j;
+            pool_tok[i] = cand_ids[f * width + j];
+            pool_par[i] = p;
+            pool_score[i] = (p >= 0 ? pool_score[p] : 0.0) + cand_logp[f * width + j];
+        }
+    double prev = INFINITY, worst = INFINITY;
+    int prev_i = -1;
+    for (int j = 0; j <= width && j < n_new + 1; ++j) {
+        int best = -1;
+        for (int i = n_pool; i < n_pool + n_new; ++i) {
+            const int after_prev = pool_score[i] < prev || (pool_score[i] == prev && i > prev_i);
+            if (!after_prev) continue;
+            if (best < 0 || pool_score[i] > pool_score[best]) best = i;
+        }
+        if (best < 0) break;
+        if (j > 0 && prev - pool_score[best] < worst) worst = prev - pool_score[best];
+        if (j < width) front_out[j] = best;
+        prev = pool_score[best];
+        prev_i = best;
+    }
+    if (margin) *margin = worst;
+    return n_pool + n_new;
+}
+
+/* Final selection: the `total` best pool nodes (score, then lower pool index), renumbered in
+ * pool order.  Outputs parent [total] (-1 = child of the root), ids [total], pool_index [total].
+ * Returns the number of nodes kept (min(total, n_pool)); -1 if the kept set is not closed under
+ * ancestors (cannot happen for log-probabilities <= 0). */
+int oracle_tree_select(const int32_t *pool_tok, const int32_t *pool_par, const double *pool_score,
+                       int n_pool, int total, int32_t *parent, int32_t *ids, int32_t *pool_index,
+                       double *margin)
+{
+    const int keep = total < n_pool ? total : n_pool;
+    char *sel = (char *)calloc((size_t)(n_pool > 0 ? n_pool : 1), 1);
+    double prev = INFINITY, worst = INFINITY;
+    int prev_i = -1;
+    for (int j = 0; j <= keep; ++j) {
+        int best = -1;
+        for (int i = 0; i < n_pool; ++i) {
+            const int after_prev = pool_score[i] < prev || (pool_score[i] == prev && i > prev_i);
+            if (!after_prev) continue;
+            if (best < 0 || pool_score[i] > pool_score[best]) best = i;
+        }
+        if (best < 0) break;
+        if (j > 0 && prev - pool_score[best] < worst) worst = prev - pool_score[best];
+        if (j < keep) sel[best] = 1;
+        prev = pool_score[best];
+        prev_i = best;
+    }
+    int n = 0, rc = keep;
+    int32_t *new_id = (int32_t *)malloc(sizeof(int32_t) * (size_t)(n_pool > 0 ? n_pool : 1));
+    for (int i = 0; i < n_pool; ++i) {
+        new_id[i] = -1;
+        if (!sel[i]) continue;
+        const int p = pool_par[i];
+        if (p >= 0 && !sel[p]) rc = -1;
+        new_id[i] = n;
+        parent[n] = p >= 0 ? new_id[p] : -1;
+        ids[n] = pool_tok[i];
+        pool_index[n] = i;
+        ++n;
+    }
+    if (margin) *margin = worst;
+    free(sel);
+    free(new_id);
+    return rc;
+}
