@@ -181,8 +181,27 @@ def main() -> int:
     def accept_sample():
         sp.accept_sample(hidden, lm_head, draft_ids, None, 1, n_q, 1.0, s_ua, s_ub, workspace=ws_s,
                          outputs=s_out)
+    # dynamic draft tree, configuration 30-4-8 (not part of `value`): top-8 log-probabilities of 8
+    # frontier rows over the full vocabulary, one level expansion, final selection
+    t_hid = hidden[:8].contiguous()
+    t_ws = torch.empty(int(sp.lib.sparrow_draft_topk_workspace(1, 8, cfg.hidden, cfg.vocab, 8)),
+                       dtype=torch.uint8, device="cuda")
+    t_pool = sp.TreePool(8, 4)
+    t_ids, t_lp = sp.draft_topk(t_hid, lm_head, 8, workspace=t_ws)
+    t_pool.expand(t_ids[:1].contiguous(), t_lp[:1].contiguous())
+    for _ in range(3):
+        t_pool.expand(t_ids, t_lp)
+    torch.cuda.synchronize()
+    def topk_call():
+        sp.draft_topk(t_hid, lm_head, 8, workspace=t_ws)
+    def tree_tail():                       # the last level's expansion and the selection
+        t_pool.n = 8 + 2 * 64
+        t_pool.expand(t_ids, t_lp)
+        t_pool.select(30)
     if args.profile_only:
         fc_many(); qkv_many(); commit_many()    # the kernels around the step, for the trace
+        for _ in range(5):
+            topk_call(); tree_tail()
         for _ in range(5):
             accept_sample()
         torch.cuda.synchronize()
@@ -216,6 +235,8 @@ def main() -> int:
     us_draft = time_graph(capture(draft_many), 20) / 28
     us_accept = time_graph(capture(accept), 20)
     us_accept_sample = time_graph(capture(accept_sample), 20)
+    us_topk = time_graph(capture(topk_call), 20)
+    us_tree_tail = time_graph(capture(tree_tail), 50)
 
     us_fc = time_graph(capture(fc_many), 20) / (2 * n_copies)
     us_qkv = time_graph(capture(qkv_many), 20) / (2 * n_copies)
@@ -270,6 +291,8 @@ def main() -> int:
                         "draft_qkv_append_gbps": round(bytes_qkv / us_qkv * 1e-3, 1)},
         "kv_commit_us": round(us_commit, 2),
         "accept_sample_t1_us": round(us_accept_sample, 2),
+        "draft_tree_30_4_8": {"draft_topk_8rows_us": round(us_topk, 2),
+                              "expand_plus_select_us": round(us_tree_tail, 2)},
         "roofline": {"bound": "hbm", "kernel": "verify_partial_mfma_kernel (split-context partial "
                                                "pass of verify attention, one layer per launch)",
                      "achieved": round(gbps_partial, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",

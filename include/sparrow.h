@@ -6,6 +6,7 @@
  *   sparrow_verify_attn         target model's verification attention
  *   sparrow_accept              lm_head GEMM -> per-row argmax -> greedy acceptance
  *   sparrow_accept_sample       the same at temperature > 0 (rejection rule + bonus draw)
+ *   sparrow_draft_topk / sparrow_tree_expand / sparrow_tree_select   dynamic draft tree
  * and, one step upstream of the draft attention,
  *   sparrow_hsr_fc              draft input by hidden state reuse
  *   sparrow_draft_qkv_append    draft layer norm / QKV / rotary step + K/V append
@@ -204,6 +205,48 @@ int sparrow_accept_sample(int32_t dtype, const void *hidden_rows, const void *lm
                           const float *u_bonus, int32_t *accept_len, int32_t *accept_path,
                           int32_t *bonus_id, void *workspace, size_t workspace_bytes,
                           void *hip_stream);
+
+/*
+ * Dynamic draft tree (Experiment section: dynamic tree structure with the
+ * configuration "total tokens - depth - width", e.g. 30-4-8; the procedure is
+ * not printed, the best-first expansion of the tree-speculation work the paper
+ * builds on is implemented).  A node's score is the sum of the draft's
+ * log-probabilities along its path.  Level 0: the `width` most likely tokens
+ * after the root.  Level d: every frontier node proposes its `width` most
+ * likely next tokens; all candidates join the pool, the `width` best of them
+ * form the next frontier.  At the end the `total` best pool nodes are kept
+ * (closed under ancestors, because log-probabilities are <= 0) and renumbered
+ * in pool order, which gives parent[i] < i as sparrow_verify_attn expects.
+ * "Better" is everywhere: higher value, then lower index / token id.
+ * The draft's forward pass between two levels is the caller's.
+ *
+ * sparrow_draft_topk: logits = hidden_rows . lm_head^T; per row the k largest
+ *   logits in decreasing order with their natural-log softmax values.
+ *   hidden_rows dev [M, hidden], lm_head dev [vocab, hidden]; ids dev int32 out [M, k];
+ *   logp dev float out [M, k]; workspace dev >= sparrow_draft_topk_workspace() bytes, 256-byte
+ *   aligned.  Limits: M <= 64, 1 <= k <= 16, k <= vocab <= 262,144.
+ * sparrow_tree_expand: one level.  front_in dev int32 [n_front] pool indices of the frontier (NULL
+ *   at level 0: the root, n_front = 1); cand_ids dev int32 / cand_logp dev float [n_front, width]
+ *   (rows of sparrow_draft_topk for the frontier nodes); the candidates are appended to the pool
+ *   arrays (pool_tok, pool_par dev int32, pool_score dev float, each with room for n_pool +
+ *   n_front*width entries) at n_pool in (frontier, candidate) order; front_out dev int32 [width]
+ *   receives the pool indices of the next frontier, best first (width <= n_front*width).
+ *   Limits: width, n_front <= 16; pool size <= 2048.
+ * sparrow_tree_select: keeps the min(total, n_pool) best nodes: parent, ids, pool_index dev int32
+ *   out, one entry per kept node in pool order.  Limits: total <= 64, n_pool <= 2048.
+ */
+size_t sparrow_draft_topk_workspace(int32_t dtype, int32_t M, int32_t hidden, int32_t vocab,
+                                    int32_t k);
+int sparrow_draft_topk(int32_t dtype, const void *hidden_rows, const void *lm_head, int32_t M,
+                       int32_t hidden, int32_t vocab, int32_t k, int32_t *ids, float *logp,
+                       void *workspace, size_t workspace_bytes, void *hip_stream);
+int sparrow_tree_expand(int32_t n_front, int32_t width, const int32_t *front_in,
+                        const int32_t *cand_ids, const float *cand_logp, int32_t *pool_tok,
+                        int32_t *pool_par, float *pool_score, int32_t n_pool, int32_t *front_out,
+                        void *hip_stream);
+int sparrow_tree_select(const int32_t *pool_tok, const int32_t *pool_par, const float *pool_score,
+                        int32_t n_pool, int32_t total, int32_t *parent, int32_t *ids,
+                        int32_t *pool_index, void *hip_stream);
 
 /*
  * Input of the draft model by hidden state reuse (Section "Visually-Aware

@@ -77,6 +77,16 @@ def _load() -> ctypes.CDLL:
     L.sparrow_accept_sample.argtypes = [ctypes.c_int32, vp, vp, vp, vp, ctypes.c_int32, ctypes.c_int32,
                                         ctypes.c_int32, ctypes.c_int32, ctypes.c_float, vp, vp,
                                         vp, vp, vp, vp, ctypes.c_size_t, vp]
+    L.sparrow_draft_topk_workspace.restype = ctypes.c_size_t
+    L.sparrow_draft_topk_workspace.argtypes = [ctypes.c_int32] * 5
+    L.sparrow_draft_topk.restype = ctypes.c_int
+    L.sparrow_draft_topk.argtypes = [ctypes.c_int32, vp, vp, ctypes.c_int32, ctypes.c_int32,
+                                     ctypes.c_int32, ctypes.c_int32, vp, vp, vp, ctypes.c_size_t, vp]
+    L.sparrow_tree_expand.restype = ctypes.c_int
+    L.sparrow_tree_expand.argtypes = [ctypes.c_int32, ctypes.c_int32, vp, vp, vp, vp, vp, vp,
+                                      ctypes.c_int32, vp, vp]
+    L.sparrow_tree_select.restype = ctypes.c_int
+    L.sparrow_tree_select.argtypes = [vp, vp, vp, ctypes.c_int32, ctypes.c_int32, vp, vp, vp, vp]
     return L
 
 
@@ -343,3 +353,62 @@ def accept_sample(hidden_rows, lm_head, draft_ids, parent, B: int, n_q: int, tem
                                      _ptr(outputs["bonus_id"]), _ptr(ws),
                                      0 if ws is None else ws.numel(), _stream_ptr(stream)))
     return outputs
+
+
+def draft_topk(hidden_rows, lm_head, k: int, workspace=None, stream=None):
+    """sparrow_draft_topk: per row the k most likely tokens (int32 [M,k], decreasing) and their
+    natural-log softmax values (float32 [M,k])."""
+    M, H = hidden_rows.shape
+    V = lm_head.shape[0]
+    if lm_head.shape[1] != H or not hidden_rows.is_contiguous() or not lm_head.is_contiguous() \
+            or lm_head.dtype != hidden_rows.dtype:
+        raise ValueError("hidden_rows [M,H] and lm_head [V,H] must be contiguous and of one dtype")
+    dev = hidden_rows.device
+    code = _dtype_code(hidden_rows)
+    ws = _workspace(int(lib.sparrow_draft_topk_workspace(code, M, H, V, k)), dev, workspace)
+    ids = torch.empty((M, k), dtype=torch.int32, device=dev)
+    logp = torch.empty((M, k), dtype=torch.float32, device=dev)
+    _check(lib.sparrow_draft_topk(code, _ptr(hidden_rows), _ptr(lm_head), M, H, V, k, _ptr(ids),
+                                  _ptr(logp), _ptr(ws), 0 if ws is None else ws.numel(),
+                                  _stream_ptr(stream)))
+    return ids, logp
+
+
+class TreePool:
+    """Device-side candidate pool of the dynamic draft tree (sparrow_tree_expand / _select)."""
+
+    def __init__(self, width: int, depth: int, device="cuda"):
+        cap = width + max(depth - 1, 0) * width * width
+        self.width = width
+        self.tok = torch.zeros(cap, dtype=torch.int32, device=device)
+        self.par = torch.zeros(cap, dtype=torch.int32, device=device)
+        self.score = torch.zeros(cap, dtype=torch.float32, device=device)
+        self.n = 0
+        self.front = None
+
+    def expand(self, cand_ids, cand_logp, stream=None):
+        n_front = 1 if self.front is None else self.front.shape[0]
+        if tuple(cand_ids.shape) != (n_front, self.width) or cand_ids.dtype != torch.int32 \
+                or cand_logp.dtype != torch.float32 or cand_logp.shape != cand_ids.shape \
+                or not cand_ids.is_contiguous() or not cand_logp.is_contiguous():
+            raise ValueError("cand_ids int32 / cand_logp float32 must be contiguous [n_front, width]")
+        if self.n + n_front * self.width > self.tok.shape[0]:
+            raise ValueError("pool is full: more levels than the depth it was sized for")
+        out = torch.empty(self.width, dtype=torch.int32, device=self.tok.device)
+        _check(lib.sparrow_tree_expand(n_front, self.width, _ptr(self.front), _ptr(cand_ids),
+                                       _ptr(cand_logp), _ptr(self.tok), _ptr(self.par),
+                                       _ptr(self.score), self.n, _ptr(out), _stream_ptr(stream)))
+        self.n += n_front * self.width
+        self.front = out
+        return out
+
+    def select(self, total: int, stream=None):
+        keep = min(total, self.n)
+        dev = self.tok.device
+        parent = torch.empty(keep, dtype=torch.int32, device=dev)
+        ids = torch.empty(keep, dtype=torch.int32, device=dev)
+        pidx = torch.empty(keep, dtype=torch.int32, device=dev)
+        _check(lib.sparrow_tree_select(_ptr(self.tok), _ptr(self.par), _ptr(self.score), self.n,
+                                       total, _ptr(parent), _ptr(ids), _ptr(pidx),
+                                       _stream_ptr(stream)))
+        return parent, ids, pidx

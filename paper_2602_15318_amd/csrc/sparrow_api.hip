@@ -9,6 +9,7 @@
 
 #include "../../include/sparrow.h"
 #include "accept.hpp"
+#include "draft_tree.hpp"
 #include "draft_window_attn.hpp"
 #include "hsr_input.hpp"
 #include "kv_commit.hpp"
@@ -510,6 +511,116 @@ int sparrow_accept_sample(int32_t dtype, const void *hidden_rows, const void *lm
   return accept_body(dtype, hidden_rows, lm_head, draft_ids, parent, B, n_q, hidden, vocab,
                      nullptr, accept_len, accept_path, bonus_id, workspace, workspace_bytes,
                      hip_stream, &sp_);
+}
+
+// ------------------------------------------------------------------ dynamic draft tree
+static size_t topk_cand_bytes(int M, int k) { return round_up((size_t)M * kStatChunks * k * sizeof(float), 256); }
+
+size_t sparrow_draft_topk_workspace(int32_t dtype, int32_t M, int32_t hidden, int32_t vocab,
+                                    int32_t k) {
+  if (M <= 0 || hidden <= 0 || vocab <= 0 || k <= 0) return 0;
+  size_t lb, sb;
+  return sparrow_accept_workspace(dtype, 1, M - 1, hidden, vocab) + accept_sample_extra(M, vocab, &lb, &sb) +
+         2 * topk_cand_bytes(M, k);
+}
+
+int sparrow_draft_topk(int32_t dtype, const void *hidden_rows, const void *lm_head, int32_t M,
+                       int32_t hidden, int32_t vocab, int32_t k, int32_t *ids, float *logp,
+                       void *workspace, size_t workspace_bytes, void *hip_stream) {
+  g_err[0] = 0;
+  if (dtype != SPARROW_F32 && dtype != SPARROW_BF16)
+    return fail(SPARROW_ERR_UNSUPPORTED, "dtype %d is neither SPARROW_F32 nor SPARROW_BF16", dtype);
+  if (M < 0) return fail(SPARROW_ERR_INVALID_ARG, "M = %d: negative", M);
+  if (M == 0) return SPARROW_OK;
+  if (M > kAcceptMaxRows) return fail(SPARROW_ERR_UNSUPPORTED, "M = %d rows exceeds %d", M, kAcceptMaxRows);
+  if (hidden <= 0 || vocab <= 0) return fail(SPARROW_ERR_INVALID_ARG, "hidden = %d, vocab = %d", hidden, vocab);
+  if (k < 1 || k > kTreeMaxWidth || k > vocab)
+    return fail(SPARROW_ERR_UNSUPPORTED, "k = %d (supported: 1..%d, at most vocab)", k, kTreeMaxWidth);
+  if (vocab > 262144) return fail(SPARROW_ERR_UNSUPPORTED, "vocab = %d exceeds 262144 (top-k)", vocab);
+  const int per = dtype == SPARROW_BF16 ? 8 : 4;
+  if (hidden % per != 0)
+    return fail(SPARROW_ERR_UNSUPPORTED, "hidden = %d must be a multiple of %d (16-byte rows)", hidden, per);
+  if (!hidden_rows || !lm_head || !ids || !logp)
+    return fail(SPARROW_ERR_INVALID_ARG, "NULL pointer among hidden_rows/lm_head/ids/logp");
+  if (!aligned16(hidden_rows) || !aligned16(lm_head))
+    return fail(SPARROW_ERR_INVALID_ARG, "hidden_rows and lm_head must be 16-byte aligned");
+  const size_t need = sparrow_draft_topk_workspace(dtype, M, hidden, vocab, k);
+  if (!workspace || workspace_bytes < need)
+    return fail(SPARROW_ERR_WORKSPACE, "workspace of %zu bytes needed, %zu given%s", need,
+                workspace_bytes, workspace ? "" : " (NULL)");
+  if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0)
+    return fail(SPARROW_ERR_INVALID_ARG, "workspace must be 256-byte aligned");
+  const bool mfma = lm_head_mfma_supported(dtype, M, hidden, vocab);
+  const int n_cand = accept_candidates(dtype, M, hidden, vocab);
+  const size_t base = sparrow_accept_workspace(dtype, 1, M - 1, hidden, vocab);
+  size_t lb, sb;
+  const size_t extra = accept_sample_extra(M, vocab, &lb, &sb);
+  char *ws = (char *)workspace;
+  AcceptArgs a;
+  memset(&a, 0, sizeof(a));
+  a.hidden = hidden_rows; a.lm_head = lm_head;
+  a.B = 1; a.n_q = M - 1; a.M = M; a.H = hidden; a.V = vocab; a.n_cand = n_cand;
+  a.cand_val = (float *)ws;
+  a.cand_idx = (int32_t *)(ws + round_up((size_t)M * n_cand * sizeof(float), 256));
+  a.logits = (float *)(ws + base);
+  hipStream_t st = (hipStream_t)hip_stream;
+  hipError_t e = mfma ? launch_lm_head_mfma(a, st) : launch_lm_head_generic(dtype, a, st);
+  if (e != hipSuccess) return fail(SPARROW_ERR_DEVICE, "lm_head launch: %s", hipGetErrorString(e));
+  SampleArgs s;
+  memset(&s, 0, sizeof(s));
+  s.logits = a.logits;
+  s.stats = (float *)(ws + base + lb);
+  s.blk_sum = (float *)(ws + base + lb + sb);
+  s.M = M; s.V = vocab; s.inv_temp_log2 = 1.4426950408889634f;
+  e = launch_logit_stats(s, st);
+  if (e != hipSuccess) return fail(SPARROW_ERR_DEVICE, "logit statistics launch: %s", hipGetErrorString(e));
+  TopkArgs t;
+  t.logits = a.logits; t.stats = s.stats;
+  t.cand_val = (float *)(ws + base + extra);
+  t.cand_idx = (int32_t *)(ws + base + extra + topk_cand_bytes(M, k));
+  t.ids = ids; t.logp = logp; t.M = M; t.V = vocab; t.k = k;
+  e = launch_topk(t, st);
+  if (e != hipSuccess) return fail(SPARROW_ERR_DEVICE, "top-k launch: %s", hipGetErrorString(e));
+  return SPARROW_OK;
+}
+
+int sparrow_tree_expand(int32_t n_front, int32_t width, const int32_t *front_in,
+                        const int32_t *cand_ids, const float *cand_logp, int32_t *pool_tok,
+                        int32_t *pool_par, float *pool_score, int32_t n_pool, int32_t *front_out,
+                        void *hip_stream) {
+  g_err[0] = 0;
+  if (width < 1 || width > kTreeMaxWidth || n_front < 1 || n_front > kTreeMaxWidth)
+    return fail(SPARROW_ERR_UNSUPPORTED, "width = %d, n_front = %d (supported: 1..%d each)", width, n_front, kTreeMaxWidth);
+  if (n_pool < 0 || n_pool + n_front * width > kTreeMaxPool)
+    return fail(SPARROW_ERR_UNSUPPORTED, "pool of %d + %d entries exceeds %d", n_pool, n_front * width, kTreeMaxPool);
+  if (!cand_ids || !cand_logp || !pool_tok || !pool_par || !pool_score || !front_out)
+    return fail(SPARROW_ERR_INVALID_ARG, "NULL pointer among the candidate / pool / frontier arrays");
+  if (!front_in && (n_front != 1 || n_pool != 0))
+    return fail(SPARROW_ERR_INVALID_ARG, "front_in may only be NULL at level 0 (n_front = 1, n_pool = 0)");
+  ExpandArgs a;
+  a.front_in = front_in; a.cand_ids = cand_ids; a.cand_logp = cand_logp;
+  a.pool_tok = pool_tok; a.pool_par = pool_par; a.pool_score = pool_score; a.front_out = front_out;
+  a.n_front = n_front; a.width = width; a.n_pool = n_pool;
+  const hipError_t e = launch_tree_expand(a, (hipStream_t)hip_stream);
+  if (e != hipSuccess) return fail(SPARROW_ERR_DEVICE, "tree expand launch: %s", hipGetErrorString(e));
+  return SPARROW_OK;
+}
+
+int sparrow_tree_select(const int32_t *pool_tok, const int32_t *pool_par, const float *pool_score,
+                        int32_t n_pool, int32_t total, int32_t *parent, int32_t *ids,
+                        int32_t *pool_index, void *hip_stream) {
+  g_err[0] = 0;
+  if (n_pool < 0 || n_pool > kTreeMaxPool) return fail(SPARROW_ERR_UNSUPPORTED, "n_pool = %d (0..%d)", n_pool, kTreeMaxPool);
+  if (total < 0 || total > SPARROW_MAX_NQ) return fail(SPARROW_ERR_UNSUPPORTED, "total = %d (0..%d)", total, SPARROW_MAX_NQ);
+  if (n_pool == 0 || total == 0) return SPARROW_OK;
+  if (!pool_tok || !pool_par || !pool_score || !parent || !ids || !pool_index)
+    return fail(SPARROW_ERR_INVALID_ARG, "NULL pointer among the pool / output arrays");
+  SelectArgs a;
+  a.pool_tok = pool_tok; a.pool_par = pool_par; a.pool_score = pool_score;
+  a.parent = parent; a.ids = ids; a.pool_index = pool_index; a.n_pool = n_pool; a.total = total;
+  const hipError_t e = launch_tree_select(a, (hipStream_t)hip_stream);
+  if (e != hipSuccess) return fail(SPARROW_ERR_DEVICE, "tree select launch: %s", hipGetErrorString(e));
+  return SPARROW_OK;
 }
 
 }  // extern "C"
