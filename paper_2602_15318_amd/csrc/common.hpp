@@ -41,6 +41,18 @@ __device__ __forceinline__ unsigned int pack_bf16x2(float lo, float hi) {
   return __builtin_bit_cast(unsigned int, v);
 }
 
+// fp16 pairs (round to nearest even) and back.
+__device__ __forceinline__ unsigned int pack_f16x2(float lo, float hi) {
+  typedef __attribute__((ext_vector_type(2))) _Float16 f16x2;
+  const f16x2 v = {(_Float16)lo, (_Float16)hi};
+  return __builtin_bit_cast(unsigned int, v);
+}
+__device__ __forceinline__ f32x4 unpack_f16x4(unsigned int w0, unsigned int w1) {
+  typedef __attribute__((ext_vector_type(2))) _Float16 f16x2;
+  const f16x2 a = __builtin_bit_cast(f16x2, w0), b = __builtin_bit_cast(f16x2, w1);
+  return (f32x4){(float)a[0], (float)a[1], (float)b[0], (float)b[1]};
+}
+
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 __device__ __forceinline__ float fast_log2(float x) { return __builtin_amdgcn_logf(x); }
 

@@ -26,7 +26,8 @@ struct VerifyArgs {
   int64_t stride_tok, stride_head;
   // plain-ALU path: part_o [n_slots, n_q, Hq, d], part_ml [n_slots, n_q, Hq, 2];
   // matrix-core path: tiled per (split, KV head, row block), see verify_attn_mfma.hip
-  float *part_o;          // unnormalised partial outputs
+  float *part_o;          // partial outputs (plain-ALU path: unnormalised fp32; matrix-core
+                          // path: normalised fp16)
   float *part_ml;         // running max (log2 domain), partial sum
   void *out;              // [B*n_q, Hq, d]
   float *lse;             // [B*n_q, Hq] or nullptr

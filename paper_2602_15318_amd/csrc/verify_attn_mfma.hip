@@ -353,8 +353,8 @@ verify_partial_mfma_kernel(VerifyArgs a, SeqTable tab, int rbs) {
   }
 
   // ---- merge the two streams (stream 1 -> LDS -> stream 0) and write the split's partials in
-  // register layout: [slot][kv head][row block][wavefront][mt][lane] x 4 floats, so that every
-  // store instruction writes 1 KB of contiguous memory.
+  // register layout: [slot][kv head][row block][wavefront][pair of d-tiles][lane] x 8 halves, so
+  // that every store instruction writes 1 KB of contiguous memory.
   f32x4 *mo = reinterpret_cast<f32x4 *>(lds);                                  // [w][mt][lane]
   float *mm = reinterpret_cast<float *>(lds + 4 * 8 * 64 * 16);                // [w][lane][m,l]
 #pragma unroll
@@ -372,49 +372,55 @@ verify_partial_mfma_kernel(VerifyArgs a, SeqTable tab, int rbs) {
       const float m1 = mm[(w * 64 + lane) * 2], l1 = mm[(w * 64 + lane) * 2 + 1];
       const float m_new = fmaxf(m_run[qt], m1);
       const float a0 = fast_exp2(m_run[qt] - m_new), a1 = fast_exp2(m1 - m_new);
-      // unit = (split, KV head, block of 64 rows)
+      // unit = (split, KV head, block of 64 rows).  The split's output is stored normalised
+      // (o / l, of the magnitude of V) in fp16, two d-tiles per 16-byte store; m and l in fp32.
       const int64_t unit = ((int64_t)slot * a.Hkv + c) * rbs64 + rb * kQT + qt;
-      f32x4 *po = reinterpret_cast<f32x4 *>(a.part_o) + (unit * 4 + w) * (8 * 64) + lane;
+      const float l_tot = l_mine * a0 + l1 * a1;
+      const float inv_l = l_tot > 0.f ? 1.0f / l_tot : 0.f;
+      const float s0 = a0 * inv_l, s1 = a1 * inv_l;
+      u32x4 *po = reinterpret_cast<u32x4 *>(a.part_o) + (unit * 4 + w) * (4 * 64) + lane;
 #pragma unroll
-      for (int mt = 0; mt < 8; ++mt) {
-        const f32x4 o1 = mo[(w * 8 + mt) * 64 + lane];
-        po[mt * 64] = o_acc[qt][mt] * a0 + o1 * a1;
+      for (int pr = 0; pr < 4; ++pr) {
+        const f32x4 x = o_acc[qt][2 * pr] * s0 + mo[(w * 8 + 2 * pr) * 64 + lane] * s1;
+        const f32x4 y = o_acc[qt][2 * pr + 1] * s0 + mo[(w * 8 + 2 * pr + 1) * 64 + lane] * s1;
+        po[pr * 64] = (u32x4){pack_f16x2(x[0], x[1]), pack_f16x2(x[2], x[3]),
+                              pack_f16x2(y[0], y[1]), pack_f16x2(y[2], y[3])};
       }
       if (c4 == 0) {
         float *pml = a.part_ml + (unit * kRowsPerWG + 16 * w + n) * 2;
         pml[0] = m_new;
-        pml[1] = l_mine * a0 + l1 * a1;
+        pml[1] = l_tot;
       }
     }
   }
 }
 
 // Combine for the tiled partial layout above.  One workgroup (4 wavefronts) per (sequence, KV head,
-// 16-row tile, 16-wide d tile); wavefront ws merges splits ws, ws+4, ... with 16 splits (1 KB
-// contiguous each) in flight at a time, so the usual 64 splits cost one memory round trip; the four
-// running results are merged through LDS.
+// 16-row tile, pair of 16-wide d tiles); wavefront ws merges splits ws, ws+4, ... with 16 splits
+// (1 KB contiguous each) in flight at a time, so the usual 64 splits cost one memory round trip;
+// the four running results are merged through LDS.
 constexpr int kCombInFlight = 16;
 
 __global__ void __launch_bounds__(256)
 verify_combine_tiled_kernel(VerifyArgs a, SeqTable tab, int rbs) {
-  __shared__ f32x4 xo[4][64];
+  __shared__ f32x4 xo[4][2][64];
   __shared__ float xm[4][64], xl[4][64];
   const int unit_in_seq = blockIdx.x;            // (c * rbs + rb) * 4 + wq
   const int wq = unit_in_seq & 3, crb = unit_in_seq >> 2;
   const int rb = crb % rbs, c = crb / rbs;
-  const int mt = blockIdx.y;
+  const int pr = blockIdx.y;                     // d-tiles 2 pr and 2 pr + 1
   const int b = blockIdx.z;
   const int ws = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int n = lane & 15, c4 = lane >> 4;
   const int g = a.Hq / a.Hkv, R = a.n_q * g;
   if (rb * kRowsPerWG + 16 * wq >= R) return;    // tile without rows (uniform)
   const int s0 = tab.cu_split[b], s1 = tab.cu_split[b + 1];
-  const f32x4 *po = reinterpret_cast<const f32x4 *>(a.part_o);
+  const u32x4 *po = reinterpret_cast<const u32x4 *>(a.part_o);
   float m_run = kNegBig, l_run = 0.f;
-  f32x4 o = {0.f, 0.f, 0.f, 0.f};
+  f32x4 o0 = {0.f, 0.f, 0.f, 0.f}, o1 = {0.f, 0.f, 0.f, 0.f};
   for (int sb = s0 + ws; sb < s1; sb += 4 * kCombInFlight) {
     float ms[kCombInFlight], ls[kCombInFlight];
-    f32x4 pa[kCombInFlight];
+    u32x4 pa[kCombInFlight];
 #pragma unroll
     for (int u = 0; u < kCombInFlight; ++u) {
       const int s = min(sb + 4 * u, s1 - 1);
@@ -422,25 +428,28 @@ verify_combine_tiled_kernel(VerifyArgs a, SeqTable tab, int rbs) {
       const float *pml = a.part_ml + (unit * kRowsPerWG + 16 * wq + n) * 2;
       ms[u] = pml[0];
       ls[u] = pml[1];
-      pa[u] = po[((unit * 4 + wq) * 8 + mt) * 64 + lane];
+      pa[u] = po[((unit * 4 + wq) * 4 + pr) * 64 + lane];
     }
     float mx = m_run;
 #pragma unroll
     for (int u = 0; u < kCombInFlight; ++u) if (sb + 4 * u < s1) mx = fmaxf(mx, ms[u]);
     const float alpha = fast_exp2(m_run - mx);
     m_run = mx;
-    l_run *= alpha; o *= alpha;
+    l_run *= alpha; o0 *= alpha; o1 *= alpha;
 #pragma unroll
     for (int u = 0; u < kCombInFlight; ++u) {
-      const float wgt = (sb + 4 * u < s1) ? fast_exp2(ms[u] - mx) : 0.f;
-      l_run = fmaf(ls[u], wgt, l_run);
-      o += pa[u] * wgt;
+      // weight of the split: its share of the softmax denominator (its output is normalised)
+      const float wgt = (sb + 4 * u < s1) ? fast_exp2(ms[u] - mx) * ls[u] : 0.f;
+      l_run += wgt;
+      o0 += unpack_f16x4(pa[u].x, pa[u].y) * wgt;
+      o1 += unpack_f16x4(pa[u].z, pa[u].w) * wgt;
     }
   }
-  xo[ws][lane] = o;
+  xo[ws][0][lane] = o0;
+  xo[ws][1][lane] = o1;
   xm[ws][lane] = m_run; xl[ws][lane] = l_run;
   __syncthreads();
-  if (ws == 0) {
+  if (ws < 2) {                                   // wavefront 0: d-tile 2 pr, wavefront 1: 2 pr + 1
     const float m = fmaxf(fmaxf(xm[0][lane], xm[1][lane]), fmaxf(xm[2][lane], xm[3][lane]));
     float l = 0.f;
     f32x4 r = {0.f, 0.f, 0.f, 0.f};
@@ -448,17 +457,17 @@ verify_combine_tiled_kernel(VerifyArgs a, SeqTable tab, int rbs) {
     for (int k = 0; k < 4; ++k) {
       const float wgt = fast_exp2(xm[k][lane] - m);
       l = fmaf(xl[k][lane], wgt, l);
-      r += xo[k][lane] * wgt;
+      r += xo[k][ws][lane] * wgt;
     }
     const int rho = rb * kRowsPerWG + 16 * wq + n;
     if (rho < R) {
       const int i_row = rho / g, h = c * g + rho % g;
       const int64_t orow = ((int64_t)b * a.n_q + i_row) * a.Hq + h;
       const float inv = 1.0f / l;
-      bf16_t *out = (bf16_t *)a.out + orow * 128 + 16 * mt + 4 * c4;
+      bf16_t *out = (bf16_t *)a.out + orow * 128 + 16 * (2 * pr + ws) + 4 * c4;
       u32x2 w0 = {pack_bf16x2(r[0] * inv, r[1] * inv), pack_bf16x2(r[2] * inv, r[3] * inv)};
       *reinterpret_cast<u32x2 *>(out) = w0;
-      if (a.lse != nullptr && mt == 0 && c4 == 0) a.lse[orow] = (m + fast_log2(l)) * kLn2;
+      if (a.lse != nullptr && pr == 0 && ws == 0 && c4 == 0) a.lse[orow] = (m + fast_log2(l)) * kLn2;
     }
   }
 }
@@ -470,7 +479,7 @@ bool verify_partial_mfma_supported(int dtype, int head_dim) {
 }
 
 // Floats of workspace per (split, KV head, row block) unit of the tiled partial layout.
-int64_t verify_mfma_unit_floats_o() { return 4 * 8 * 64 * 4; }
+int64_t verify_mfma_unit_floats_o() { return 4 * 4 * 64 * 4; }   // 16 KB: 64 rows x 128 halves
 int64_t verify_mfma_unit_floats_ml() { return kRowsPerWG * 2; }
 
 // Row blocks per (split, KV head): workgroups of 64 rows for R <= 64, of 128 rows beyond.
@@ -497,7 +506,7 @@ hipError_t launch_verify_partial_mfma(const VerifyArgs &a, const SeqTable &tab, 
 hipError_t launch_verify_combine_mfma(const VerifyArgs &a, const SeqTable &tab, hipStream_t st) {
   const int R = a.n_q * (a.Hq / a.Hkv);
   const int rbs = (R + kRowsPerWG - 1) / kRowsPerWG;
-  dim3 grid(a.Hkv * rbs * 4, 8, a.B);
+  dim3 grid(a.Hkv * rbs * 4, 4, a.B);
   hipLaunchKernelGGL(verify_combine_tiled_kernel, grid, dim3(256), 0, st, a, tab, rbs);
   return hipGetLastError();
 }
