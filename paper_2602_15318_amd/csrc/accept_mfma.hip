@@ -49,16 +49,9 @@ lm_head_mfma_kernel(AcceptArgs a, int row0) {
     const int qq = min(q, max(nq - 1, 0));
     const int j = qq / chunks_per_tile, cidx = qq - j * chunks_per_tile;
     const int v = min((gw + j * n_waves) * 16 + n, V - 1);
-#ifdef LM_EXP_LINEAR   // bandwidth experiment: same bytes, fully sequential per wavefront (wrong results)
-    const bf16_t *p = Wm + (int64_t)min((gw + j * n_waves) * 16, V - 16) * H + cidx * (512 * kLmChunk) + 8 * lane;
-#pragma unroll
-    for (int s = 0; s < kLmChunk; ++s) buf[s] = __builtin_nontemporal_load((const u32x4 *)(p + 512 * s));
-    (void)v;
-#else
     const bf16_t *p = Wm + (int64_t)v * H + cidx * (32 * kLmChunk) + 8 * c4;
 #pragma unroll
     for (int s = 0; s < kLmChunk; ++s) buf[s] = __builtin_nontemporal_load((const u32x4 *)(p + 32 * s));
-#endif
   };
   u32x4 bufA[kLmChunk], bufB[kLmChunk];
   issue(0, bufA);

@@ -23,7 +23,8 @@ def lib():
     L.sparrow_last_error.restype = ctypes.c_char_p
     L.sparrow_version.restype = ctypes.c_char_p
     for f in ("sparrow_draft_window_attn_workspace", "sparrow_verify_attn_workspace",
-              "sparrow_accept_workspace"):
+              "sparrow_accept_workspace", "sparrow_accept_sample_workspace",
+              "sparrow_draft_topk_workspace"):
         getattr(L, f).restype = ctypes.c_size_t
     return L
 
@@ -117,11 +118,95 @@ def test_accept_argument_validation(lib):
 def test_workspace_queries(lib):
     d = desc()
     v = lib.sparrow_verify_attn_workspace(ctypes.byref(d), 1, 8, ctypes.c_int64(26120))
-    # about one split per compute unit: 64 splits x 4 KV heads x 32.5 KB
-    assert 7 * 2 ** 20 < v < 10 * 2 ** 20
+    # about one split per compute unit: 64 splits x 4 KV heads x 16.5 KB (fp16 partials, fp32 m/l)
+    assert 64 * 4 * 16.5 * 1024 <= v < 5 * 2 ** 20
+    # a 30-node tree has 210 rows per KV head: two workgroups of 128 rows per (split, KV head),
+    # planned in whole groups per XCD: 32 splits x 4 heads x 4 units of 64 rows
+    t = lib.sparrow_verify_attn_workspace(ctypes.byref(d), 1, 30, ctypes.c_int64(26142))
+    assert 32 * 4 * 4 * 16.5 * 1024 <= t < 12 * 2 ** 20
+    # K/V beyond 2 GB per call: the plain-ALU path with its own layout (fp32 [split, n_q, Hq, d])
+    big = lib.sparrow_verify_attn_workspace(ctypes.byref(d), 8, 8, ctypes.c_int64(3_000_000))
+    assert big > 0 and big % 256 == 0
     assert lib.sparrow_verify_attn_workspace(ctypes.byref(d), 0, 8, ctypes.c_int64(26120)) == 0
     f32 = desc(dtype=0, hq=4, hkv=1, d=64)
     assert lib.sparrow_verify_attn_workspace(ctypes.byref(f32), 1, 4, ctypes.c_int64(516)) > 0
     a = lib.sparrow_accept_workspace(1, 1, 8, 3584, 152064)
     assert 0 < a < 2 ** 20
     assert lib.sparrow_accept_workspace(0, 1, 4, 256, 1024) > 0
+
+
+def test_draft_input_argument_validation(lib):
+    fc = lambda dtype=1, M=1, H=3584, V=1000, emb=P, tok=P: lib.sparrow_hsr_fc(
+        i32(dtype), emb, tok, P, P, None, i32(M), i32(H), i32(V), P, None)
+    assert fc(dtype=5) == UNSUPPORTED
+    assert fc(M=65) == UNSUPPORTED and b"65" in lib.sparrow_last_error()
+    assert fc(H=3580) == UNSUPPORTED
+    assert fc(V=0) == INVALID
+    assert fc(emb=None) == INVALID
+    assert fc(emb=ctypes.c_void_p(0x10004)) == INVALID
+    assert fc(M=0) == OK
+    rows, rp = _cu(5, 9)
+    qkv = lambda d, M=2, H=3584, eps=1e-6, kv=rp, cos=P: lib.sparrow_draft_qkv_append(
+        ctypes.byref(d), P, P, ctypes.c_float(eps), P, None, cos, P, kv, i32(M), i32(H), P, P, P, None)
+    assert qkv(desc(d=96)) == UNSUPPORTED
+    assert qkv(desc(), M=65) == UNSUPPORTED
+    assert qkv(desc(), eps=-1.0) == INVALID
+    assert qkv(desc(), cos=None) == INVALID
+    assert qkv(desc(), cos=ctypes.c_void_p(0x10004)) == INVALID
+    dup, dp_ = _cu(7, 7)
+    assert qkv(desc(), kv=dp_) == INVALID and b"same cache row" in lib.sparrow_last_error()
+    neg, np_ = _cu(3, -2)
+    assert qkv(desc(), kv=np_) == INVALID
+    assert qkv(desc(), M=0) == OK
+
+
+def test_commit_argument_validation(lib):
+    cu, cup = _cu(0, 50)
+    ptrs = (ctypes.c_void_p * 2)(0x10000, 0x20000)
+    call = lambda d, nl=2, B=1, n_q=8, cu_=cup, hid=None, H=0, nxt=None, k=ptrs: lib.sparrow_kv_commit(
+        ctypes.byref(d), k, ptrs, i32(nl), cu_, i32(B), i32(n_q), P, P, hid, i32(H), nxt, None)
+    assert call(desc(), nl=65) == UNSUPPORTED
+    assert call(desc(), B=65) == UNSUPPORTED
+    assert call(desc(), n_q=65) == UNSUPPORTED
+    short, sp_ = _cu(0, 5)
+    assert call(desc(), cu_=sp_) == INVALID and b"fewer" in lib.sparrow_last_error()
+    assert call(desc(), hid=P, H=3584) == INVALID          # next_hidden missing
+    assert call(desc(), hid=P, H=3, nxt=P) == UNSUPPORTED  # rows not multiples of 16 bytes
+    bad = (ctypes.c_void_p * 2)(0x10000, 0x20004)
+    assert call(desc(), k=bad) == INVALID
+    assert call(desc(), B=0) == OK
+    assert call(desc(), nl=0) == OK
+
+
+def test_accept_sample_and_tree_argument_validation(lib):
+    samp = lambda T=1.0, V=152064, ws=None, wsb=0, ua=P: lib.sparrow_accept_sample(
+        i32(1), P, P, P, None, i32(1), i32(8), i32(3584), i32(V), ctypes.c_float(T), ua, P, P, P, P,
+        ws, ctypes.c_size_t(wsb), None)
+    assert samp(T=0.0) == INVALID and b"temperature" in lib.sparrow_last_error()
+    assert samp(T=float("inf")) == INVALID
+    assert samp(V=(1 << 20) + 1) == UNSUPPORTED
+    assert samp(ua=None) == INVALID
+    assert samp() == WORKSPACE
+    need = lib.sparrow_accept_sample_workspace(1, 1, 8, 3584, 152064)
+    greedy = lib.sparrow_accept_workspace(1, 1, 8, 3584, 152064)
+    assert need >= greedy + 9 * 152064 * 4                 # the stored logits
+    topk = lambda M=8, k=8, V=152064, ws=None, wsb=0: lib.sparrow_draft_topk(
+        i32(1), P, P, i32(M), i32(3584), i32(V), i32(k), P, P, ws, ctypes.c_size_t(wsb), None)
+    assert topk(k=17) == UNSUPPORTED
+    assert topk(k=0) == UNSUPPORTED
+    assert topk(M=65) == UNSUPPORTED
+    assert topk(V=300000) == UNSUPPORTED
+    assert topk(V=4, k=8) == UNSUPPORTED                   # more tokens asked for than there are
+    assert topk() == WORKSPACE
+    assert topk(M=0) == OK
+    assert lib.sparrow_draft_topk_workspace(1, 8, 3584, 152064, 8) > 8 * 152064 * 4
+    exp = lambda nf=1, w=8, fin=None, npool=0: lib.sparrow_tree_expand(
+        i32(nf), i32(w), fin, P, P, P, P, P, i32(npool), P, None)
+    assert exp(w=17) == UNSUPPORTED
+    assert exp(nf=17, fin=P) == UNSUPPORTED
+    assert exp(nf=8, fin=P, npool=2040) == UNSUPPORTED     # pool capacity 2048
+    assert exp(nf=2) == INVALID and b"level 0" in lib.sparrow_last_error()
+    sel = lambda n=200, total=30: lib.sparrow_tree_select(P, P, P, i32(n), i32(total), P, P, P, None)
+    assert sel(total=65) == UNSUPPORTED
+    assert sel(n=2049) == UNSUPPORTED
+    assert sel(n=0) == OK and sel(total=0) == OK
