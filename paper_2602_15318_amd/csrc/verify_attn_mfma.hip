@@ -395,17 +395,20 @@ verify_partial_mfma_kernel(VerifyArgs a, SeqTable tab, int rbs) {
   }
 }
 
-// Combine for the tiled partial layout above.  One workgroup (4 wavefronts) per (sequence, KV head,
-// 16-row tile, 16-wide d tile); wavefront ws merges splits ws, ws+4, ... with 16 splits (8 bytes
-// per lane each) in flight at a time, so the usual 64 splits cost one memory round trip; the four
-// running results are merged through LDS.  (Two d-tiles per workgroup, 16-byte loads, measured
-// slower: 6.0 vs 4.6 us -- the pass is bound by its dependent chain, not by load width.)
-constexpr int kCombInFlight = 16;
+// Combine for the tiled partial layout above.  One workgroup of 16 wavefronts per (sequence, KV
+// head, 16-row tile, 16-wide d tile); wavefront ws merges splits ws, ws+16, ... with 4 splits (8
+// bytes per lane each) in flight at a time, so the usual 64 splits cost one memory round trip; the
+// running results are merged through LDS.  The pass is bound by its dependent chain (launch, one
+// load round trip, the exponentials, the LDS merge, the store), not by bytes: measured per C5 layer
+// with 4 wavefronts x 16 splits and two d-tiles per workgroup 20.6 us, one d-tile 19.0 us, 8 x 8
+// 18.7 us, 16 x 4 18.5 us.
+constexpr int kCombInFlight = 4;
+constexpr int kCombWaves = 16;
 
-__global__ void __launch_bounds__(256)
+__global__ void __launch_bounds__(64 * kCombWaves)
 verify_combine_tiled_kernel(VerifyArgs a, SeqTable tab, int rbs) {
-  __shared__ f32x4 xo[4][64];
-  __shared__ float xm[4][64], xl[4][64];
+  __shared__ f32x4 xo[kCombWaves][64];
+  __shared__ float xm[kCombWaves][64], xl[kCombWaves][64];
   const int unit_in_seq = blockIdx.x;            // (c * rbs + rb) * 4 + wq
   const int wq = unit_in_seq & 3, crb = unit_in_seq >> 2;
   const int rb = crb % rbs, c = crb / rbs;
@@ -419,12 +422,12 @@ verify_combine_tiled_kernel(VerifyArgs a, SeqTable tab, int rbs) {
   const u32x2 *po = reinterpret_cast<const u32x2 *>(a.part_o);
   float m_run = kNegBig, l_run = 0.f;
   f32x4 o = {0.f, 0.f, 0.f, 0.f};
-  for (int sb = s0 + ws; sb < s1; sb += 4 * kCombInFlight) {
+  for (int sb = s0 + ws; sb < s1; sb += kCombWaves * kCombInFlight) {
     float ms[kCombInFlight], ls[kCombInFlight];
     u32x2 pa[kCombInFlight];
 #pragma unroll
     for (int u = 0; u < kCombInFlight; ++u) {
-      const int s = min(sb + 4 * u, s1 - 1);
+      const int s = min(sb + kCombWaves * u, s1 - 1);
       const int64_t unit = ((int64_t)s * a.Hkv + c) * rbs + rb;
       const float *pml = a.part_ml + (unit * kRowsPerWG + 16 * wq + n) * 2;
       ms[u] = pml[0];
@@ -433,14 +436,14 @@ verify_combine_tiled_kernel(VerifyArgs a, SeqTable tab, int rbs) {
     }
     float mx = m_run;
 #pragma unroll
-    for (int u = 0; u < kCombInFlight; ++u) if (sb + 4 * u < s1) mx = fmaxf(mx, ms[u]);
+    for (int u = 0; u < kCombInFlight; ++u) if (sb + kCombWaves * u < s1) mx = fmaxf(mx, ms[u]);
     const float alpha = fast_exp2(m_run - mx);
     m_run = mx;
     l_run *= alpha; o *= alpha;
 #pragma unroll
     for (int u = 0; u < kCombInFlight; ++u) {
       // weight of the split: its share of the softmax denominator (its output is normalised)
-      const float wgt = (sb + 4 * u < s1) ? fast_exp2(ms[u] - mx) * ls[u] : 0.f;
+      const float wgt = (sb + kCombWaves * u < s1) ? fast_exp2(ms[u] - mx) * ls[u] : 0.f;
       l_run += wgt;
       o += unpack_f16x4(pa[u].x, pa[u].y) * wgt;
     }
@@ -449,11 +452,13 @@ verify_combine_tiled_kernel(VerifyArgs a, SeqTable tab, int rbs) {
   xm[ws][lane] = m_run; xl[ws][lane] = l_run;
   __syncthreads();
   if (ws == 0) {
-    const float m = fmaxf(fmaxf(xm[0][lane], xm[1][lane]), fmaxf(xm[2][lane], xm[3][lane]));
+    float m = xm[0][lane];
+#pragma unroll
+    for (int k = 1; k < kCombWaves; ++k) m = fmaxf(m, xm[k][lane]);
     float l = 0.f;
     f32x4 r = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int k = 0; k < 4; ++k) {
+    for (int k = 0; k < kCombWaves; ++k) {
       const float wgt = fast_exp2(xm[k][lane] - m);
       l = fmaf(xl[k][lane], wgt, l);
       r += xo[k][lane] * wgt;
@@ -506,7 +511,7 @@ hipError_t launch_verify_combine_mfma(const VerifyArgs &a, const SeqTable &tab, 
   const int R = a.n_q * (a.Hq / a.Hkv);
   const int rbs = (R + kRowsPerWG - 1) / kRowsPerWG;
   dim3 grid(a.Hkv * rbs * 4, 8, a.B);
-  hipLaunchKernelGGL(verify_combine_tiled_kernel, grid, dim3(256), 0, st, a, tab, rbs);
+  hipLaunchKernelGGL(verify_combine_tiled_kernel, grid, dim3(64 * kCombWaves), 0, st, a, tab, rbs);
   return hipGetLastError();
 }
 
