@@ -100,7 +100,10 @@ def test_verify_trees(sp, oracle, dtype, Hq, Hkv, d):
     lay = (((wl.TEXT, 700),), ((wl.TEXT, 90),))
     trees = [wl.chain_parent(7), np.full(5, -1, dtype=np.int32),
              wl.pruned_tree(1, 25, (4, 2, 2, 1, 1)), wl.pruned_tree(2, 30, (8, 2, 1, 1)),
-             wl.pruned_tree(3, 48, (10, 2, 2, 1, 1)), wl.pruned_tree(4, 64, (4, 4, 2, 2, 1, 1))]
+             wl.pruned_tree(3, 48, (10, 2, 2, 1, 1)), wl.pruned_tree(4, 64, (4, 4, 2, 2, 1, 1)),
+             # 70 and 133 rows per KV head at 28/4 heads: a 128-row workgroup whose second row
+             # tile is nearly empty, and a second workgroup with five rows
+             wl.pruned_tree(5, 10, (3, 2, 2)), wl.pruned_tree(6, 19, (4, 3, 2))]
     for ti, parent in enumerate(trees):
         c = wl.verify_case(cfg, seed=50 + ti, layouts=lay, n_q=len(parent), parent=parent)
         _verify_and_check(sp, oracle, c, f"tree {ti} ({len(parent)} nodes) {dtype}")
