@@ -92,3 +92,78 @@ def test_partial_then_combine_equals_single_call(sp, dtype, Hq, Hkv, d):
     sp.verify_attn(q, k, v, c.cu_seqlens, None, 6, out=out, lse=lse, workspace=ws, passes=2)
     torch.cuda.synchronize()
     assert torch.equal(out, ref) and torch.equal(lse, ref_lse)
+
+
+def test_graph_replay_of_the_surrounding_steps(sp):
+    """Draft input, dynamic tree, acceptance at T = 1 and commit in one captured graph: replays
+    with scribbled workspaces and outputs in between reproduce the eager results bit for bit."""
+    import torch
+    cfg = wl.Config("G2", "bf16", 28, 4, 128, 1,
+                    (((wl.TEXT, 60), (wl.VISUAL, 800), (wl.TEXT, 40)),), 64, 6, False, 3584, 4096)
+    n_q, H, V = cfg.n_q, cfg.hidden, cfg.vocab
+    hc = wl.hsr_case(cfg, 5, rows=1, vocab=V)
+    d = wl.draft_case(cfg, 5)
+    v = wl.verify_case(cfg, 5)
+    a = wl.accept_case(cfg, 5, planted=True)
+    bf = "bf16"
+    emb, tok, hp = dev(hc.embed, bf), dev(hc.token_ids), dev(hc.h_prev, bf)
+    wfc, bfc, g_, wqkv, bqkv = (dev(hc.w_fc, bf), dev(hc.b_fc, bf), dev(hc.norm_weight, bf),
+                                dev(hc.w_qkv, bf), dev(hc.b_qkv, bf))
+    cs, sn = dev(hc.rope_cos), dev(hc.rope_sin)
+    dk, dv = dev(d.k, bf), dev(d.v, bf)
+    kv_row = np.array([int(d.cu_seqlens[1]) - 1], dtype=np.int32)
+    vk, vv = dev(v.k, bf), dev(v.v, bf)
+    hid, W = dev(a.hidden, bf), dev(a.lm_head, bf)
+    draft = a.planted_ids[:n_q].copy()
+    draft[3] = (draft[3] + 1) % V
+    draft = dev(draft)
+    ua = torch.full((1, n_q), 0.01, device="cuda")
+    ub = torch.full((1,), 0.5, device="cuda")
+    ws_s = torch.empty(sp.accept_sample_workspace_bytes(1, 1, n_q, H, V), dtype=torch.uint8, device="cuda")
+    ws_t = torch.empty(int(sp.lib.sparrow_draft_topk_workspace(1, n_q + 1, H, V, 4)), dtype=torch.uint8,
+                       device="cuda")
+
+    def make():
+        return {"z": torch.zeros(1, H, dtype=torch.bfloat16, device="cuda"),
+                "q": torch.zeros(1, 28, 128, dtype=torch.bfloat16, device="cuda"),
+                "s": {"accept_len": torch.zeros(1, dtype=torch.int32, device="cuda"),
+                      "accept_path": torch.zeros(1, n_q, dtype=torch.int32, device="cuda"),
+                      "bonus_id": torch.zeros(1, dtype=torch.int32, device="cuda")},
+                "next": torch.zeros(1, H, dtype=torch.bfloat16, device="cuda"),
+                "k": vk.clone(), "v": vv.clone(), "dk": dk.clone(), "dv": dv.clone()}
+
+    def step(o):
+        sp.hsr_fc(emb, tok, hp, wfc, bfc, out=o["z"])
+        sp.draft_qkv_append(o["z"], g_, hc.eps, wqkv, bqkv, cs, sn, kv_row, 28, o["dk"], o["dv"], q_out=o["q"])
+        ids, lp = sp.draft_topk(hid, W, 4, workspace=ws_t)
+        o["ids"], o["lp"] = ids, lp
+        sp.accept_sample(hid, W, draft, None, 1, n_q, 1.0, ua, ub, workspace=ws_s, outputs=o["s"])
+        sp.kv_commit([o["k"]], [o["v"]], v.cu_seqlens, n_q, o["s"]["accept_path"], o["s"]["accept_len"],
+                     hidden_rows=hid, next_hidden=o["next"])
+
+    eager = make()
+    step(eager)
+    torch.cuda.synchronize()
+    assert eager["s"]["accept_len"].item() == 3          # planted, u = 0.01: three drafts accepted
+    cap = make()
+    g = torch.cuda.CUDAGraph()
+    s = torch.cuda.Stream()
+    s.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(s):
+        step(cap)
+    torch.cuda.current_stream().wait_stream(s)
+    torch.cuda.synchronize()
+    with torch.cuda.graph(g):
+        step(cap)
+    for rep in range(3):
+        for t in (cap["z"], cap["q"], cap["next"], cap["ids"], cap["lp"], *cap["s"].values()):
+            t.zero_()
+        cap["k"].copy_(vk); cap["v"].copy_(vv); cap["dk"].copy_(dk); cap["dv"].copy_(dv)
+        ws_s.random_(0, 255); ws_t.random_(0, 255)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        for key in ("z", "q", "next", "k", "v", "dk", "dv", "ids", "lp"):
+            assert torch.equal(cap[key], eager[key]), f"{key} differs on replay {rep}"
+        for key in eager["s"]:
+            assert torch.equal(cap["s"][key], eager["s"][key]), f"{key} differs on replay {rep}"
