@@ -61,7 +61,11 @@ def main() -> int:
     with ThreadPoolExecutor(max_workers=8) as pool:
         cases = list(pool.map(lambda l: wl.verify_case(cfg, args.seed, layer=l), range(cfg.n_layers)))
     cu = cases[0].cu_seqlens
-    layers = [(dev(c.q, bf16), dev(c.k, bf16), dev(c.v, bf16)) for c in cases]
+    def head_major(x):
+        # [T, Hkv, d] view of a [Hkv, T, d] allocation: every KV head's tokens are contiguous, so a
+        # workgroup (one KV head, one split) streams one contiguous 100 KB range of K and of V
+        return dev(x, bf16).permute(1, 0, 2).contiguous().permute(1, 0, 2)
+    layers = [(dev(c.q, bf16), head_major(c.k), head_major(c.v)) for c in cases]
     if args.no_cpu_baseline:
         cases = cases[:1]            # the oracle leg walks every layer; otherwise free the host copies
     dcase = wl.draft_case(cfg, args.seed)
@@ -274,7 +278,8 @@ def main() -> int:
         "config": {"workload": "C5: 28 layers x verify attn (28/4 heads, d128, chain k=8, ctx "
                                "26,112 = 512 text + 25,088 visual + 512 text) + draft window attn "
                                "(W=512) + lm_head 152,064x3584 on 9 rows + argmax + greedy accept",
-                   "batch": 1, "seed": args.seed, "launch": "HIP graph replay"},
+                   "batch": 1, "seed": args.seed, "launch": "HIP graph replay",
+                   "kv_layout": "head-major [Hkv, T, d] per layer (the library also takes token-major)"},
         "bytes_per_step": bytes_step,
         "us_per_step": round(us_step, 2),
         "verify_attn_us_per_step": round(us_verify_step, 2),

@@ -44,11 +44,17 @@ int check_desc(const sparrow_attn_desc *d) {
   if (d->head_dim != 64 && d->head_dim != 128)
     return fail(SPARROW_ERR_UNSUPPORTED, "head_dim %d (supported: 64, 128)", d->head_dim);
   const int per = d->dtype == SPARROW_BF16 ? 8 : 4;
+  // token-major ([T, Hkv, d]: a token's heads side by side) or head-major ([Hkv, T, d]: a head's
+  // tokens side by side; that stride_head covers all tokens is the caller's precondition)
+  const bool token_major = d->kv_stride_token >= d->kv_stride_head * d->n_kv_heads;
+  const bool head_major = d->kv_stride_head >= d->kv_stride_token;
   if (d->kv_stride_head < d->head_dim || d->kv_stride_head % per != 0 ||
-      d->kv_stride_token < d->kv_stride_head * d->n_kv_heads || d->kv_stride_token % per != 0)
+      d->kv_stride_token < d->head_dim || d->kv_stride_token % per != 0 ||
+      !(token_major || head_major))
     return fail(SPARROW_ERR_INVALID_ARG,
-                "kv strides (token %lld, head %lld) must be multiples of 16 bytes with "
-                "stride_head >= head_dim and stride_token >= n_kv_heads*stride_head",
+                "kv strides (token %lld, head %lld) must be multiples of 16 bytes, at least "
+                "head_dim, and either stride_token >= n_kv_heads*stride_head (token-major) or "
+                "stride_head >= stride_token (head-major)",
                 (long long)d->kv_stride_token, (long long)d->kv_stride_head);
   if (!(d->scale >= 0.f) || std::isinf(d->scale))
     return fail(SPARROW_ERR_INVALID_ARG, "scale must be finite and >= 0 (0 = 1/sqrt(head_dim))");
