@@ -31,6 +31,7 @@ constexpr int kRowBytes = 256;            // one K or V row of a head: 128 bf16
 constexpr int kTileBytes = kTile * kRowBytes;
 constexpr int kSub = 1;                   // 32-token tiles per stream per step
 constexpr int kRowsPerWG = 64;
+constexpr int kMlFloats = 3;              // per row of a partial: max, sum, output scale
 constexpr int kStreams = 2;
 constexpr float kSlack = 8.0f;            // log2 units a score may exceed a row's reference point
 
@@ -373,23 +374,39 @@ verify_partial_mfma_kernel(VerifyArgs a, SeqTable tab, int rbs) {
       const float m_new = fmaxf(m_run[qt], m1);
       const float a0 = fast_exp2(m_run[qt] - m_new), a1 = fast_exp2(m1 - m_new);
       // unit = (split, KV head, block of 64 rows).  The split's output is stored normalised
-      // (o / l, of the magnitude of V) in fp16, two d-tiles per 16-byte store; m and l in fp32.
+      // (o / l: a convex combination of V rows, of the magnitude of V) in fp16, two d-tiles per
+      // 16-byte store; m, l and a per-row power-of-two scale c in fp32.  c is 1 unless the row's
+      // largest |o / l| would leave the fp16 range (|V| beyond 16384), then o / (l c) is stored.
       const int64_t unit = ((int64_t)slot * a.Hkv + c) * rbs64 + rb * kQT + qt;
       const float l_tot = l_mine * a0 + l1 * a1;
       const float inv_l = l_tot > 0.f ? 1.0f / l_tot : 0.f;
       const float s0 = a0 * inv_l, s1 = a1 * inv_l;
+      float amax = 0.f;
+#pragma unroll
+      for (int mt = 0; mt < 8; ++mt) {
+        o_acc[qt][mt] = o_acc[qt][mt] * s0 + mo[(w * 8 + mt) * 64 + lane] * s1;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) amax = fmaxf(amax, fabsf(o_acc[qt][mt][i]));
+      }
+      amax = quad_max(amax);                       // over the row's 128 values
+      float cscale = 1.0f, inv_c = 1.0f;
+      if (amax > 16384.f) {                        // exponent of amax / 16384, rounded up
+        const int e = (int)((__float_as_uint(amax) >> 23) & 0xff) - 127 - 13;
+        cscale = __uint_as_float((unsigned int)(127 + e) << 23);
+        inv_c = __uint_as_float((unsigned int)(127 - e) << 23);
+      }
       u32x4 *po = reinterpret_cast<u32x4 *>(a.part_o) + (unit * 4 + w) * (4 * 64) + lane;
 #pragma unroll
       for (int pr = 0; pr < 4; ++pr) {
-        const f32x4 x = o_acc[qt][2 * pr] * s0 + mo[(w * 8 + 2 * pr) * 64 + lane] * s1;
-        const f32x4 y = o_acc[qt][2 * pr + 1] * s0 + mo[(w * 8 + 2 * pr + 1) * 64 + lane] * s1;
+        const f32x4 x = o_acc[qt][2 * pr] * inv_c, y = o_acc[qt][2 * pr + 1] * inv_c;
         po[pr * 64] = (u32x4){pack_f16x2(x[0], x[1]), pack_f16x2(x[2], x[3]),
                               pack_f16x2(y[0], y[1]), pack_f16x2(y[2], y[3])};
       }
       if (c4 == 0) {
-        float *pml = a.part_ml + (unit * kRowsPerWG + 16 * w + n) * 2;
+        float *pml = a.part_ml + (unit * kRowsPerWG + 16 * w + n) * kMlFloats;
         pml[0] = m_new;
         pml[1] = l_tot;
+        pml[2] = cscale;
       }
     }
   }
@@ -423,15 +440,16 @@ verify_combine_tiled_kernel(VerifyArgs a, SeqTable tab, int rbs) {
   float m_run = kNegBig, l_run = 0.f;
   f32x4 o = {0.f, 0.f, 0.f, 0.f};
   for (int sb = s0 + ws; sb < s1; sb += kCombWaves * kCombInFlight) {
-    float ms[kCombInFlight], ls[kCombInFlight];
+    float ms[kCombInFlight], ls[kCombInFlight], cs[kCombInFlight];
     u32x2 pa[kCombInFlight];
 #pragma unroll
     for (int u = 0; u < kCombInFlight; ++u) {
       const int s = min(sb + kCombWaves * u, s1 - 1);
       const int64_t unit = ((int64_t)s * a.Hkv + c) * rbs + rb;
-      const float *pml = a.part_ml + (unit * kRowsPerWG + 16 * wq + n) * 2;
+      const float *pml = a.part_ml + (unit * kRowsPerWG + 16 * wq + n) * kMlFloats;
       ms[u] = pml[0];
       ls[u] = pml[1];
+      cs[u] = pml[2];
       pa[u] = po[((((unit * 4 + wq) * 4 + (mt >> 1)) * 64 + lane) << 1) + (mt & 1)];
     }
     float mx = m_run;
@@ -445,7 +463,7 @@ verify_combine_tiled_kernel(VerifyArgs a, SeqTable tab, int rbs) {
       // weight of the split: its share of the softmax denominator (its output is normalised)
       const float wgt = (sb + kCombWaves * u < s1) ? fast_exp2(ms[u] - mx) * ls[u] : 0.f;
       l_run += wgt;
-      o += unpack_f16x4(pa[u].x, pa[u].y) * wgt;
+      o += unpack_f16x4(pa[u].x, pa[u].y) * (wgt * cs[u]);
     }
   }
   xo[ws][lane] = o;
@@ -484,7 +502,7 @@ bool verify_partial_mfma_supported(int dtype, int head_dim) {
 
 // Floats of workspace per (split, KV head, row block) unit of the tiled partial layout.
 int64_t verify_mfma_unit_floats_o() { return 4 * 4 * 64 * 4; }   // 16 KB: 64 rows x 128 halves
-int64_t verify_mfma_unit_floats_ml() { return kRowsPerWG * 2; }
+int64_t verify_mfma_unit_floats_ml() { return kRowsPerWG * kMlFloats; }
 
 // Row blocks per (split, KV head): workgroups of 64 rows for R <= 64, of 128 rows beyond.
 int verify_mfma_row_blocks(int R) { return R <= kRowsPerWG ? 1 : (R + 2 * kRowsPerWG - 1) / (2 * kRowsPerWG); }

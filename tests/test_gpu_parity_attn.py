@@ -183,6 +183,26 @@ def test_head_major_kv_layout(sp, oracle):
         check_attn(host(out), ref, dtype, f"head-major draft {dtype}")
 
 
+def test_large_v_does_not_overflow_the_split_partials(sp, oracle):
+    """The matrix-core path keeps the split outputs as fp16 with a per-row power-of-two scale:
+    V of magnitude 2^20 and 2^100 (far outside fp16) must come out as exactly that multiple of
+    the ordinary result, with the usual relative error."""
+    cfg = _cfg("bf16", 28, 4, 128)
+    lay = (((wl.TEXT, 50), (wl.VISUAL, 2100), (wl.TEXT, 77)),)
+    c = wl.verify_case(cfg, seed=91, layouts=lay, n_q=8, parent=None)
+    base, _ = run_verify(sp, c)
+    for p2 in (20, 100):
+        c2 = wl.verify_case(cfg, seed=91, layouts=lay, n_q=8, parent=None)
+        c2.v = (c2.v.astype(np.float64) * 2.0 ** p2).astype(np.float32)        # exact in bf16
+        out, _ = run_verify(sp, c2)
+        assert np.all(np.isfinite(out))
+        ref, _ = oracle.verify_attn(c2.q, c2.k, c2.v, c2.cu_seqlens, None, 8)
+        scale = np.abs(ref).max()
+        assert np.abs(out - ref).max() <= 2e-2 * scale, f"2^{p2}"
+        # same bits as the unscaled run, shifted by the exponent
+        np.testing.assert_array_equal(out, base * 2.0 ** p2)
+
+
 def test_argument_errors(sp):
     import torch
     from gpu_util import dev
