@@ -256,6 +256,18 @@ def main() -> int:
         for l in range(cfg.n_layers):
             verify_layer(l, passes=1)
     us_partial = time_graph(capture(partial_all), max(5, args.steps // 2)) / cfg.n_layers
+    # context for that figure: a kernel that only reads the same K and V bytes (one launch per
+    # layer over the layer's K storage, one over its V storage would be two launches; K and V of
+    # a layer are separate allocations, so the read is timed as two half-size launches and as
+    # the pair)
+    k_flat = [k.permute(1, 0, 2) for _, k, _ in layers]                  # the head-major storage
+    v_flat = [v.permute(1, 0, 2) for _, _, v in layers]
+    sink = torch.zeros(1, dtype=torch.int32, device="cuda")
+    def read_all():
+        for l in range(cfg.n_layers):
+            sp.stream_read(k_flat[l], sink)
+            sp.stream_read(v_flat[l], sink)
+    us_plain_read = time_graph(capture(read_all), max(5, args.steps // 2)) / cfg.n_layers
     gbps_partial = bytes_verify_layer / us_partial * 1e-3
     us_layer = us_verify_step / cfg.n_layers       # partial + combine, back to back in a graph
     gbps_layer = bytes_verify_layer / us_layer * 1e-3
@@ -303,7 +315,11 @@ def main() -> int:
                      "achieved": round(gbps_partial, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(gbps_partial / HBM_PEAK_GBPS, 4), "traffic": traffic,
                      "algorithmic_bytes_per_launch": bytes_verify_layer,
-                     "avg_launch_us": round(us_partial, 3)},
+                     "avg_launch_us": round(us_partial, 3),
+                     "plain_read_of_the_same_kv_us": round(us_plain_read, 3),
+                     "plain_read_note": "sparrow_stream_read over the layer's K and over its V "
+                                        "storage (two launches per layer, nothing but 16-byte "
+                                        "non-temporal loads): what moving these bytes costs here"},
         "context": "paper: 2.82x average decoding speedup, LLaVA-OneVision-7B on NVIDIA L20, 25K "
                    "visual tokens, T=0 (end-to-end, other hardware; not comparable)",
         "input_gen_s": round(t_gen, 1),

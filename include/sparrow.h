@@ -333,6 +333,15 @@ int sparrow_kv_commit(const sparrow_attn_desc *desc, void *const *k_layers, void
                       const void *hidden_rows, int32_t hidden, void *next_hidden,
                       void *hip_stream);
 
+/*
+ * Measurement aid (no part of the method): enqueues a kernel that reads `bytes` bytes at `dev_ptr`
+ * once, with the same 16-byte non-temporal loads the attention kernels use, and does nothing
+ * else; bench.py times it on a layer's K and V to show what moving those bytes costs on the
+ * device at hand.  dev_ptr 16-byte aligned, bytes a multiple of 16; sink dev, 4 bytes, may be
+ * written.
+ */
+int sparrow_stream_read(const void *dev_ptr, size_t bytes, void *sink, void *hip_stream);
+
 /* Thread-local description of the last error on this thread; "" if none. */
 const char *sparrow_last_error(void);
 

@@ -87,6 +87,8 @@ def _load() -> ctypes.CDLL:
                                       ctypes.c_int32, vp, vp]
     L.sparrow_tree_select.restype = ctypes.c_int
     L.sparrow_tree_select.argtypes = [vp, vp, vp, ctypes.c_int32, ctypes.c_int32, vp, vp, vp, vp]
+    L.sparrow_stream_read.restype = ctypes.c_int
+    L.sparrow_stream_read.argtypes = [vp, ctypes.c_size_t, vp, vp]
     return L
 
 
@@ -412,3 +414,10 @@ class TreePool:
                                        total, _ptr(parent), _ptr(ids), _ptr(pidx),
                                        _stream_ptr(stream)))
         return parent, ids, pidx
+
+
+def stream_read(t: torch.Tensor, sink: torch.Tensor, stream=None) -> None:
+    """sparrow_stream_read over the storage of a contiguous tensor (measurement aid)."""
+    if not t.is_contiguous():
+        raise ValueError("stream_read needs a contiguous tensor")
+    _check(lib.sparrow_stream_read(_ptr(t), t.numel() * t.element_size(), _ptr(sink), _stream_ptr(stream)))

@@ -17,6 +17,7 @@
 
 namespace sparrow {
 int generic_num_candidates(int V);
+hipError_t launch_stream_read(const void *p, size_t bytes, unsigned int *sink, hipStream_t st);
 
 namespace {
 thread_local char g_err[512] = "";
@@ -233,6 +234,16 @@ int sparrow_kv_commit(const sparrow_attn_desc *desc, void *const *k_layers, void
   a.H = hidden; a.esize = esize;
   const hipError_t e = launch_kv_commit(a, (hipStream_t)hip_stream);
   if (e != hipSuccess) return fail(SPARROW_ERR_DEVICE, "kv_commit launch: %s", hipGetErrorString(e));
+  return SPARROW_OK;
+}
+
+int sparrow_stream_read(const void *dev_ptr, size_t bytes, void *sink, void *hip_stream) {
+  g_err[0] = 0;
+  if (bytes == 0) return SPARROW_OK;
+  if (!dev_ptr || !sink || !aligned16(dev_ptr) || bytes % 16 != 0)
+    return fail(SPARROW_ERR_INVALID_ARG, "stream_read: NULL or misaligned pointer, or bytes not a multiple of 16");
+  const hipError_t e = launch_stream_read(dev_ptr, bytes, (unsigned int *)sink, (hipStream_t)hip_stream);
+  if (e != hipSuccess) return fail(SPARROW_ERR_DEVICE, "stream_read launch: %s", hipGetErrorString(e));
   return SPARROW_OK;
 }
 

@@ -210,3 +210,13 @@ def test_accept_sample_and_tree_argument_validation(lib):
     assert sel(total=65) == UNSUPPORTED
     assert sel(n=2049) == UNSUPPORTED
     assert sel(n=0) == OK and sel(total=0) == OK
+
+
+def test_stream_read_argument_validation(lib):
+    lib.sparrow_stream_read.restype = ctypes.c_int
+    call = lambda p, n, sink=P: lib.sparrow_stream_read(p, ctypes.c_size_t(n), sink, None)
+    assert call(None, 0) == OK
+    assert call(None, 64) == INVALID
+    assert call(P, 40) == INVALID                          # not a multiple of 16
+    assert call(ctypes.c_void_p(0x10004), 64) == INVALID   # misaligned
+    assert call(P, 64, sink=None) == INVALID

@@ -167,3 +167,20 @@ def test_graph_replay_of_the_surrounding_steps(sp):
             assert torch.equal(cap[key], eager[key]), f"{key} differs on replay {rep}"
         for key in eager["s"]:
             assert torch.equal(cap["s"][key], eager["s"][key]), f"{key} differs on replay {rep}"
+
+
+def test_stream_read_runs_and_leaves_its_input_alone(sp):
+    """The measurement aid reads a buffer and writes nothing but (at most) its 4-byte sink."""
+    import torch
+    x = torch.arange(1 << 20, dtype=torch.int32, device="cuda")
+    keep = x.clone()
+    sink = torch.zeros(1, dtype=torch.int32, device="cuda")
+    for n in (4, 1 << 10, (1 << 20) - 4, 1 << 20):        # ragged tails of the unrolled loop
+        sp.stream_read(x[:n], sink)
+    torch.cuda.synchronize()
+    assert torch.equal(x, keep)
+    # the loads are live: one 16-byte load whose words XOR to all ones reaches the sink
+    w = torch.tensor([-1, 0, 0, 0], dtype=torch.int32, device="cuda")
+    sp.stream_read(w, sink)
+    torch.cuda.synchronize()
+    assert int(sink.item()) == -1
