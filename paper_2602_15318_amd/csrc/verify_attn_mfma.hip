@@ -70,9 +70,15 @@ __device__ __forceinline__ float quad_sum(float v) {
 // steps at decode-time sizes (7 at 26k context on 256 compute units), so a deep look-ahead turns
 // the kernel into "load most of it, then compute": depth 1 is fastest there, depth 2 once the
 // splits get long (batches, very long contexts).
+// Per-sequence split length in tokens (split_len of the sequence), worked out by the host so that
+// the kernel's way to its first load holds no integer division.
+struct PieceTable {
+  int32_t piece[SPARROW_MAX_BATCH];
+};
+
 template <int kPrefetch, int kQT>
 __global__ void __launch_bounds__(256 * kStreams)
-verify_partial_mfma_kernel(VerifyArgs a, SeqTable tab, int rbs) {
+verify_partial_mfma_kernel(VerifyArgs a, SeqTable tab, PieceTable pt, int rbs) {
   // [stream][buf][K,V][kSub tiles]; after the main loop the first 34 KB are reused for the merge
   extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
   constexpr int kStepBytes = kSub * kTileBytes;            // K (or V) rows of one stream step
@@ -86,46 +92,41 @@ verify_partial_mfma_kernel(VerifyArgs a, SeqTable tab, int rbs) {
   const int strm = wave_id >> 2, w = wave_id & 3;
   const int tid = threadIdx.x & 255, lane = threadIdx.x & 63;
   const int n = lane & 15, c4 = lane >> 4;
-  // Workgroup -> (split, KV head, row block).  Workgroups are handed to the 8 XCDs round-robin by
-  // their linear index, and the row blocks of one (split, KV head) stream the same K/V: they get
-  // indices that are equal modulo 8 and adjacent in that XCD's order, so they run at the same time
-  // on one XCD and all but the first fetch of a tile hit its L2.  (Only the speed depends on the
-  // round-robin placement.)
+  // Workgroup -> (sequence, KV head, split of the sequence, row block): grid (x, KV head,
+  // sequence), so that everything the first K/V load needs comes from ONE round of scalar loads
+  // of the arguments (the sequence's entries of the tables are addressed by blockIdx.z) and no
+  // division -- at decode-time sizes the whole kernel lasts ~13 us and every dependent round trip
+  // before the first load shows.  x: workgroups are handed to the 8 XCDs round-robin by their
+  // linear index and gridDim.x is a multiple of 8, so x & 7 is the XCD; the row blocks of one
+  // split stream the same K/V and get x values that are equal modulo 8 and adjacent in that
+  // XCD's order: they run at the same time on one XCD and all but the first fetch of a tile hit
+  // its L2.  (Only the speed depends on the round-robin placement.)
+  const int b = blockIdx.z, c = blockIdx.y;
+  const int cl0 = tab.cu_len[b], len = tab.cu_len[b + 1] - cl0;
+  const int cs0 = tab.cu_split[b], ns = tab.cu_split[b + 1] - cs0;
+  const int piece = pt.piece[b];
+  // an empty statement that takes these values as scalar-register inputs: the compiler has to
+  // have all of them loaded here, which makes it issue their loads together, ahead of the
+  // branches below, instead of one round per use
+  asm volatile("" ::"s"(rbs), "s"(cl0), "s"(len), "s"(cs0), "s"(ns), "s"(piece), "s"(a.k), "s"(a.v),
+               "s"(a.stride_tok), "s"(a.stride_head), "s"(a.n_q));
   const int xj = blockIdx.x >> 3;
-  const int rb = xj % rbs;
-  const int grp = (xj / rbs) * 8 + (blockIdx.x & 7);       // split + n_slots * KV head
-  if (grp >= a.n_slots * a.Hkv) return;                    // padding of the last round of 8
-  const int slot = grp % a.n_slots, c = grp / a.n_slots;
-  const int g = a.Hq / a.Hkv;
-  const int R = a.n_q * g;
-  const int rbs64 = (R + kRowsPerWG - 1) / kRowsPerWG;     // 64-row units of the partial layout
-  const int b = seq_of_slot(tab, a.B, slot);
-  const int len = tab.cu_len[b + 1] - tab.cu_len[b];
+  int rb = 0, sq = xj;
+  if (rbs > 1) { rb = xj % rbs; sq = xj / rbs; }
+  const int s_loc = sq * 8 + (blockIdx.x & 7);             // split within the sequence
+  if (s_loc >= ns) return;                                 // padding of the grid (uniform)
+  const int slot = cs0 + s_loc;
   const int L = len - a.n_q;
-  const int piece = split_len(len, tab.cu_split[b + 1] - tab.cu_split[b]);
-  const int t0 = min(len, (slot - tab.cu_split[b]) * piece);
+  const int t0 = min(len, s_loc * piece);
   const int t1 = min(len, t0 + piece);
   const int n_tiles = (t1 - t0 + kTile - 1) / kTile;                    // of the workgroup
   const int n_steps = (n_tiles + kStreams * kSub - 1) / (kStreams * kSub);   // loop trips
   // K/V of this sequence and head; a token row is addressed by a 32-bit byte offset from here
   // (the host checks that a sequence's K/V spans less than 2 GB)
-  const int64_t seq_off = (int64_t)tab.cu_len[b] * a.stride_tok + (int64_t)c * a.stride_head;
+  const int64_t seq_off = (int64_t)cl0 * a.stride_tok + (int64_t)c * a.stride_head;
   const unsigned char *Kg = (const unsigned char *)((const bf16_t *)a.k + seq_off);
   const unsigned char *Vg = (const unsigned char *)((const bf16_t *)a.v + seq_off);
   const unsigned int row_bytes = (unsigned int)a.stride_tok * 2u;
-
-  // ---- this lane's query rows: one per row tile
-  bool row_ok[kQT];
-  int i_row[kQT], h[kQT];
-  int n_act = 0;                                  // row tiles of this wavefront that hold rows
-#pragma unroll
-  for (int qt = 0; qt < kQT; ++qt) {
-    const int rho = (rb * kQT + qt) * kRowsPerWG + 16 * w + n;
-    row_ok[qt] = rho < R;
-    if ((rb * kQT + qt) * kRowsPerWG + 16 * w < R) n_act = qt + 1;
-    i_row[qt] = row_ok[qt] ? rho / g : 0;
-    h[qt] = row_ok[qt] ? c * g + rho % g : 0;
-  }
 
   // ---- loader: in step `st` stream `strm` owns tiles (st*kStreams + strm)*kSub .. +kSub, i.e.
   // 32*kSub consecutive tokens; thread -> rows tid/16 + 16 j, 16-byte chunk tid%16.  Rows past
@@ -157,9 +158,27 @@ verify_partial_mfma_kernel(VerifyArgs a, SeqTable tab, int rbs) {
 
   // ---- first step, then Q^T (B operand of the score MFMA: lane (n, c4) holds
   // Q[row][32*ks + 8*c4 .. +8]), then the rest of the look-ahead.
+  issue(0, stage[0]);
+  __builtin_amdgcn_sched_barrier(0);      // the first step is on its way before anything else is worked out
+
+  const int g = a.Hq / a.Hkv;
+  const int R = a.n_q * g;
+  const int rbs64 = (R + kRowsPerWG - 1) / kRowsPerWG;     // 64-row units of the partial layout
+  // ---- this lane's query rows: one per row tile
+  bool row_ok[kQT];
+  int i_row[kQT], h[kQT];
+  int n_act = 0;                                  // row tiles of this wavefront that hold rows
+#pragma unroll
+  for (int qt = 0; qt < kQT; ++qt) {
+    const int rho = (rb * kQT + qt) * kRowsPerWG + 16 * w + n;
+    row_ok[qt] = rho < R;
+    if ((rb * kQT + qt) * kRowsPerWG + 16 * w < R) n_act = qt + 1;
+    i_row[qt] = row_ok[qt] ? rho / g : 0;
+    h[qt] = row_ok[qt] ? c * g + rho % g : 0;
+  }
+
   bf16x8 qreg[kQT][4];
   {
-    issue(0, stage[0]);
     u32x4 qv[kQT][4];
 #pragma unroll
     for (int qt = 0; qt < kQT; ++qt) {
@@ -173,7 +192,7 @@ verify_partial_mfma_kernel(VerifyArgs a, SeqTable tab, int rbs) {
     // issues all its loads back to back: without this barrier the look-ahead of the wavefronts
     // that issue first would queue ahead of the FIRST step of the others (measured: 3 us of
     // skew between the two streams).
-    __syncthreads();
+    if (kPrefetch > 1) __syncthreads();
 #pragma unroll
     for (int p = 1; p < kPrefetch; ++p) issue(p, stage[p]);
     // Loads retire in order: Q (and the first step before it) have landed once at most the
@@ -423,19 +442,23 @@ constexpr int kCombInFlight = 4;
 constexpr int kCombWaves = 16;
 
 __global__ void __launch_bounds__(64 * kCombWaves)
-verify_combine_tiled_kernel(VerifyArgs a, SeqTable tab, int rbs) {
+verify_combine_tiled_kernel(VerifyArgs a, SeqTable tab, int rbs, int g) {
   __shared__ f32x4 xo[kCombWaves][64];
   __shared__ float xm[kCombWaves][64], xl[kCombWaves][64];
+  const int b = blockIdx.z;
+  const int s0 = tab.cu_split[b], s1 = tab.cu_split[b + 1];
+  // all scalar arguments in one round of loads (see the partial pass)
+  asm volatile("" ::"s"(rbs), "s"(g), "s"(s0), "s"(s1), "s"(a.n_q), "s"(a.Hq), "s"(a.Hkv), "s"(a.part_o),
+               "s"(a.part_ml), "s"(a.out), "s"(a.lse));
   const int unit_in_seq = blockIdx.x;            // (c * rbs + rb) * 4 + wq
   const int wq = unit_in_seq & 3, crb = unit_in_seq >> 2;
-  const int rb = crb % rbs, c = crb / rbs;
+  int rb = 0, c = crb;
+  if (rbs > 1) { rb = crb % rbs; c = crb / rbs; }
   const int mt = blockIdx.y;                     // d-tile: half (mt & 1) of the stored pair mt >> 1
-  const int b = blockIdx.z;
   const int ws = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int n = lane & 15, c4 = lane >> 4;
-  const int g = a.Hq / a.Hkv, R = a.n_q * g;
+  const int R = a.n_q * g;
   if (rb * kRowsPerWG + 16 * wq >= R) return;    // tile without rows (uniform)
-  const int s0 = tab.cu_split[b], s1 = tab.cu_split[b + 1];
   const u32x2 *po = reinterpret_cast<const u32x2 *>(a.part_o);
   float m_run = kNegBig, l_run = 0.f;
   f32x4 o = {0.f, 0.f, 0.f, 0.f};
@@ -510,18 +533,25 @@ int verify_mfma_row_blocks(int R) { return R <= kRowsPerWG ? 1 : (R + 2 * kRowsP
 hipError_t launch_verify_partial_mfma(const VerifyArgs &a, const SeqTable &tab, hipStream_t st) {
   const int R = a.n_q * (a.Hq / a.Hkv);
   const int rbs = verify_mfma_row_blocks(R);
-  dim3 grid((a.n_slots * a.Hkv + 7) / 8 * 8 * rbs), block(256 * kStreams);
+  PieceTable pt;
+  int max_ns = 0;
+  for (int b = 0; b < SPARROW_MAX_BATCH; ++b) {
+    const int ns = b < a.B ? tab.cu_split[b + 1] - tab.cu_split[b] : 0;
+    pt.piece[b] = ns > 0 ? split_len(tab.cu_len[b + 1] - tab.cu_len[b], ns) : 0;
+    if (ns > max_ns) max_ns = ns;
+  }
+  dim3 grid((max_ns + 7) / 8 * 8 * rbs, a.Hkv, a.B), block(256 * kStreams);
   constexpr int kLdsBytes = kStreams * 2 * 2 * kSub * kTileBytes;
   static_assert(kLdsBytes <= 64 * 1024, "beyond 64 KB the kernel needs the dynamic-LDS attribute");
   const int steps = (a.chunk / kTile + kStreams * kSub - 1) / (kStreams * kSub);   // of a full split
   if (R > kRowsPerWG && steps <= 10)
-    hipLaunchKernelGGL((verify_partial_mfma_kernel<1, 2>), grid, block, kLdsBytes, st, a, tab, rbs);
+    hipLaunchKernelGGL((verify_partial_mfma_kernel<1, 2>), grid, block, kLdsBytes, st, a, tab, pt, rbs);
   else if (R > kRowsPerWG)
-    hipLaunchKernelGGL((verify_partial_mfma_kernel<2, 2>), grid, block, kLdsBytes, st, a, tab, rbs);
+    hipLaunchKernelGGL((verify_partial_mfma_kernel<2, 2>), grid, block, kLdsBytes, st, a, tab, pt, rbs);
   else if (steps <= 10)
-    hipLaunchKernelGGL((verify_partial_mfma_kernel<1, 1>), grid, block, kLdsBytes, st, a, tab, rbs);
+    hipLaunchKernelGGL((verify_partial_mfma_kernel<1, 1>), grid, block, kLdsBytes, st, a, tab, pt, rbs);
   else
-    hipLaunchKernelGGL((verify_partial_mfma_kernel<2, 1>), grid, block, kLdsBytes, st, a, tab, rbs);
+    hipLaunchKernelGGL((verify_partial_mfma_kernel<2, 1>), grid, block, kLdsBytes, st, a, tab, pt, rbs);
   return hipGetLastError();
 }
 
@@ -529,7 +559,8 @@ hipError_t launch_verify_combine_mfma(const VerifyArgs &a, const SeqTable &tab, 
   const int R = a.n_q * (a.Hq / a.Hkv);
   const int rbs = (R + kRowsPerWG - 1) / kRowsPerWG;
   dim3 grid(a.Hkv * rbs * 4, 8, a.B);
-  hipLaunchKernelGGL(verify_combine_tiled_kernel, grid, dim3(64 * kCombWaves), 0, st, a, tab, rbs);
+  hipLaunchKernelGGL(verify_combine_tiled_kernel, grid, dim3(64 * kCombWaves), 0, st, a, tab, rbs,
+                     a.Hq / a.Hkv);
   return hipGetLastError();
 }
 
