@@ -418,14 +418,14 @@ verify_partial_mfma_kernel(VerifyArgs a, SeqTable tab, PieceTable pt, int rbs) {
 #pragma unroll
       for (int pr = 0; pr < 4; ++pr) {
         const f32x4 x = o_acc[qt][2 * pr] * inv_c, y = o_acc[qt][2 * pr + 1] * inv_c;
-        po[pr * 64] = (u32x4){pack_f16x2(x[0], x[1]), pack_f16x2(x[2], x[3]),
-                              pack_f16x2(y[0], y[1]), pack_f16x2(y[2], y[3])};
+        __builtin_nontemporal_store((u32x4){pack_f16x2(x[0], x[1]), pack_f16x2(x[2], x[3]),
+                                            pack_f16x2(y[0], y[1]), pack_f16x2(y[2], y[3])}, &po[pr * 64]);
       }
       if (c4 == 0) {
         float *pml = a.part_ml + (unit * kRowsPerWG + 16 * w + n) * kMlFloats;
-        pml[0] = m_new;
-        pml[1] = l_tot;
-        pml[2] = cscale;
+        __builtin_nontemporal_store(m_new, &pml[0]);
+        __builtin_nontemporal_store(l_tot, &pml[1]);
+        __builtin_nontemporal_store(cscale, &pml[2]);
       }
     }
   }
@@ -470,10 +470,10 @@ verify_combine_tiled_kernel(VerifyArgs a, SeqTable tab, int rbs, int g) {
       const int s = min(sb + kCombWaves * u, s1 - 1);
       const int64_t unit = ((int64_t)s * a.Hkv + c) * rbs + rb;
       const float *pml = a.part_ml + (unit * kRowsPerWG + 16 * wq + n) * kMlFloats;
-      ms[u] = pml[0];
-      ls[u] = pml[1];
-      cs[u] = pml[2];
-      pa[u] = po[((((unit * 4 + wq) * 4 + (mt >> 1)) * 64 + lane) << 1) + (mt & 1)];
+      ms[u] = __builtin_nontemporal_load(&pml[0]);
+      ls[u] = __builtin_nontemporal_load(&pml[1]);
+      cs[u] = __builtin_nontemporal_load(&pml[2]);
+      pa[u] = __builtin_nontemporal_load(&po[((((unit * 4 + wq) * 4 + (mt >> 1)) * 64 + lane) << 1) + (mt & 1)]);
     }
     float mx = m_run;
 #pragma unroll
