@@ -87,25 +87,34 @@ __global__ void __launch_bounds__(256) lm_head_generic_kernel(AcceptArgs a) {
 // chain / tree.
 __global__ void __launch_bounds__(1024) accept_finalize_kernel(AcceptArgs a) {
   __shared__ int32_t tgt[kAcceptMaxRows];
+  __shared__ int32_t dr_s[kAcceptMaxRows], par_s[kAcceptMaxRows];
   const int tid = threadIdx.x;
   const int w = tid >> 6, lane = tid & 63;
+  // draft tokens and parents of every sequence into LDS while the candidates are being reduced:
+  // the walk below is a chain of dependent reads and should not pay a memory round trip each
+  if (tid < a.B * a.n_q) {
+    const int j = tid % a.n_q;
+    dr_s[tid] = a.draft_ids[tid];
+    par_s[tid] = a.parent ? a.parent[j] : j - 1;
+  }
   for (int r = w; r < a.M; r += 16) {
     float bv = -INFINITY;
     int bi = 0x7fffffff;
     const float *cv = a.cand_val + (int64_t)r * a.n_cand;
     const int32_t *ci = a.cand_idx + (int64_t)r * a.n_cand;
-    for (int c0 = lane; c0 < a.n_cand; c0 += 64 * 8) {   // eight independent loads in flight
-      float v[8];
-      int i[8];
+    constexpr int kU = 16;                               // independent loads in flight per lane
+    for (int c0 = lane; c0 < a.n_cand; c0 += 64 * kU) {
+      float v[kU];
+      int i[kU];
 #pragma unroll
-      for (int u = 0; u < 8; ++u) {
+      for (int u = 0; u < kU; ++u) {
         const int c = c0 + 64 * u;
         const bool in = c < a.n_cand;
         v[u] = in ? cv[c] : -INFINITY;
         i[u] = in ? ci[c] : 0x7fffffff;
       }
 #pragma unroll
-      for (int u = 0; u < 8; ++u)
+      for (int u = 0; u < kU; ++u)
         if (v[u] > bv || (v[u] == bv && i[u] < bi)) { bv = v[u]; bi = i[u]; }
     }
 #pragma unroll
@@ -120,7 +129,7 @@ __global__ void __launch_bounds__(1024) accept_finalize_kernel(AcceptArgs a) {
   if (tid < a.B) {
     const int b = tid;
     const int32_t *t = tgt + b * (a.n_q + 1);
-    const int32_t *dr = a.draft_ids + (int64_t)b * a.n_q;
+    const int32_t *dr = dr_s + b * a.n_q, *par = par_s + b * a.n_q;
     int32_t *path = a.accept_path + (int64_t)b * a.n_q;
     int cur = -1, len = 0;
     // every accepted node has a larger index than its parent: at most n_q steps
@@ -128,8 +137,7 @@ __global__ void __launch_bounds__(1024) accept_finalize_kernel(AcceptArgs a) {
       const int tok = t[cur + 1];
       int next = -1;
       for (int j = cur + 1; j < a.n_q; ++j) {
-        const int pj = a.parent ? a.parent[j] : j - 1;
-        if (pj == cur && dr[j] == tok) { next = j; break; }
+        if (par[j] == cur && dr[j] == tok) { next = j; break; }
       }
       if (next < 0) break;
       path[len++] = next;
