@@ -78,7 +78,7 @@ struct PieceTable {
 
 template <int kPrefetch, int kQT>
 __global__ void __launch_bounds__(256 * kStreams)
-verify_partial_mfma_kernel(VerifyArgs a, SeqTable tab, PieceTable pt, int rbs) {
+verify_partial_mfma_kernel(VerifyArgs a, SeqTable tab, PieceTable pt, int rbs, int flat) {
   // [stream][buf][K,V][kSub tiles]; after the main loop the first 34 KB are reused for the merge
   extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
   constexpr int kStepBytes = kSub * kTileBytes;            // K (or V) rows of one stream step
@@ -92,29 +92,50 @@ verify_partial_mfma_kernel(VerifyArgs a, SeqTable tab, PieceTable pt, int rbs) {
   const int strm = wave_id >> 2, w = wave_id & 3;
   const int tid = threadIdx.x & 255, lane = threadIdx.x & 63;
   const int n = lane & 15, c4 = lane >> 4;
-  // Workgroup -> (sequence, KV head, split of the sequence, row block): grid (x, KV head,
-  // sequence), so that everything the first K/V load needs comes from ONE round of scalar loads
-  // of the arguments (the sequence's entries of the tables are addressed by blockIdx.z) and no
-  // division -- at decode-time sizes the whole kernel lasts ~13 us and every dependent round trip
-  // before the first load shows.  x: workgroups are handed to the 8 XCDs round-robin by their
-  // linear index and gridDim.x is a multiple of 8, so x & 7 is the XCD; the row blocks of one
-  // split stream the same K/V and get x values that are equal modulo 8 and adjacent in that
-  // XCD's order: they run at the same time on one XCD and all but the first fetch of a tile hit
-  // its L2.  (Only the speed depends on the round-robin placement.)
-  const int b = blockIdx.z, c = blockIdx.y;
-  const int cl0 = tab.cu_len[b], len = tab.cu_len[b + 1] - cl0;
-  const int cs0 = tab.cu_split[b], ns = tab.cu_split[b + 1] - cs0;
-  const int piece = pt.piece[b];
+  // Workgroup -> (sequence, KV head, split of the sequence, row block).  Workgroups are handed to
+  // the 8 XCDs round-robin by their linear index and gridDim.x is a multiple of 8, so x & 7 is
+  // the XCD; the row blocks of one split stream the same K/V and get x values that are equal
+  // modulo 8 and adjacent in that XCD's order: they run at the same time on one XCD and all but
+  // the first fetch of a tile hit its L2.  (Only the speed depends on the round-robin placement.)
+  // Two grid shapes:
+  //  - (x, KV head, sequence): everything the first K/V load needs comes from ONE round of scalar
+  //    loads of the arguments (the sequence's table entries are addressed by blockIdx.z) and no
+  //    division -- at decode-time sizes the whole kernel lasts ~13 us and every dependent round
+  //    trip before the first load shows.  x is sized for the sequence with the most splits; the
+  //    XCD of a split is rotated by its global number, so that the splits of all heads and
+  //    sequences together are dealt evenly to the XCDs.
+  //  - flat (x only; for ragged batches, where the first shape would launch mostly padding):
+  //    x enumerates (global split, KV head) and the sequence is searched in the split table.
+  const int xj = blockIdx.x >> 3, xcd = blockIdx.x & 7;
+  const int bz = flat ? 0 : blockIdx.z;
+  const int cl0_z = tab.cu_len[bz], cl1_z = tab.cu_len[bz + 1];
+  const int cs0_z = tab.cu_split[bz], cs1_z = tab.cu_split[bz + 1];
+  const int piece_z = pt.piece[bz];
   // an empty statement that takes these values as scalar-register inputs: the compiler has to
   // have all of them loaded here, which makes it issue their loads together, ahead of the
   // branches below, instead of one round per use
-  asm volatile("" ::"s"(rbs), "s"(cl0), "s"(len), "s"(cs0), "s"(ns), "s"(piece), "s"(a.k), "s"(a.v),
-               "s"(a.stride_tok), "s"(a.stride_head), "s"(a.n_q));
-  const int xj = blockIdx.x >> 3;
+  asm volatile("" ::"s"(rbs), "s"(flat), "s"(cl0_z), "s"(cl1_z), "s"(cs0_z), "s"(cs1_z), "s"(piece_z),
+               "s"(a.k), "s"(a.v), "s"(a.stride_tok), "s"(a.stride_head), "s"(a.n_q), "s"(a.n_slots),
+               "s"(a.Hkv));
   int rb = 0, sq = xj;
   if (rbs > 1) { rb = xj % rbs; sq = xj / rbs; }
-  const int s_loc = sq * 8 + (blockIdx.x & 7);             // split within the sequence
-  if (s_loc >= ns) return;                                 // padding of the grid (uniform)
+  int b = bz, c, s_loc;
+  int cl0 = cl0_z, len = cl1_z - cl0_z, cs0 = cs0_z, ns = cs1_z - cs0_z, piece = piece_z;
+  if (flat) {
+    const int grp = sq * 8 + xcd;                          // global split + n_slots * KV head
+    if (grp >= a.n_slots * a.Hkv) return;                  // padding of the last round of 8
+    const int gslot = grp % a.n_slots;
+    c = grp / a.n_slots;
+    b = seq_of_slot(tab, a.B, gslot);
+    cl0 = tab.cu_len[b]; len = tab.cu_len[b + 1] - cl0;
+    cs0 = tab.cu_split[b]; ns = tab.cu_split[b + 1] - cs0;
+    piece = pt.piece[b];
+    s_loc = gslot - cs0;
+  } else {
+    c = blockIdx.y;
+    s_loc = sq * 8 + ((xcd - (cs0 + a.n_slots * c)) & 7);  // split within the sequence
+    if (s_loc >= ns) return;                               // padding of the grid (uniform)
+  }
   const int slot = cs0 + s_loc;
   const int L = len - a.n_q;
   const int t0 = min(len, s_loc * piece);
@@ -540,18 +561,22 @@ hipError_t launch_verify_partial_mfma(const VerifyArgs &a, const SeqTable &tab, 
     pt.piece[b] = ns > 0 ? split_len(tab.cu_len[b + 1] - tab.cu_len[b], ns) : 0;
     if (ns > max_ns) max_ns = ns;
   }
-  dim3 grid((max_ns + 7) / 8 * 8 * rbs, a.Hkv, a.B), block(256 * kStreams);
+  // grid shape: one x range per (KV head, sequence) unless that would launch mostly padding
+  const int x3d = (max_ns + 7) / 8 * 8;
+  const int flat = (int64_t)a.n_slots * 4 < (int64_t)x3d * a.B * 3;      // fewer than 3/4 of the slots real
+  dim3 grid(x3d * rbs, a.Hkv, a.B), block(256 * kStreams);
+  if (flat) grid = dim3((a.n_slots * a.Hkv + 7) / 8 * 8 * rbs, 1, 1);
   constexpr int kLdsBytes = kStreams * 2 * 2 * kSub * kTileBytes;
   static_assert(kLdsBytes <= 64 * 1024, "beyond 64 KB the kernel needs the dynamic-LDS attribute");
   const int steps = (a.chunk / kTile + kStreams * kSub - 1) / (kStreams * kSub);   // of a full split
   if (R > kRowsPerWG && steps <= 10)
-    hipLaunchKernelGGL((verify_partial_mfma_kernel<1, 2>), grid, block, kLdsBytes, st, a, tab, pt, rbs);
+    hipLaunchKernelGGL((verify_partial_mfma_kernel<1, 2>), grid, block, kLdsBytes, st, a, tab, pt, rbs, flat);
   else if (R > kRowsPerWG)
-    hipLaunchKernelGGL((verify_partial_mfma_kernel<2, 2>), grid, block, kLdsBytes, st, a, tab, pt, rbs);
+    hipLaunchKernelGGL((verify_partial_mfma_kernel<2, 2>), grid, block, kLdsBytes, st, a, tab, pt, rbs, flat);
   else if (steps <= 10)
-    hipLaunchKernelGGL((verify_partial_mfma_kernel<1, 1>), grid, block, kLdsBytes, st, a, tab, pt, rbs);
+    hipLaunchKernelGGL((verify_partial_mfma_kernel<1, 1>), grid, block, kLdsBytes, st, a, tab, pt, rbs, flat);
   else
-    hipLaunchKernelGGL((verify_partial_mfma_kernel<2, 1>), grid, block, kLdsBytes, st, a, tab, pt, rbs);
+    hipLaunchKernelGGL((verify_partial_mfma_kernel<2, 1>), grid, block, kLdsBytes, st, a, tab, pt, rbs, flat);
   return hipGetLastError();
 }
 
