@@ -33,6 +33,9 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--other-configs", action="store_true",
+                    help="also time verify attention on the parity configurations (C2, C3, C4) and "
+                         "on the dynamic-tree shapes, and add them to the JSON line as `other_configs`")
     ap.add_argument("--profile-only", action="store_true",
                     help="run warmup + steps only (for rocprofv3), skip the per-op timing legs")
     args = ap.parse_args()
@@ -324,6 +327,40 @@ def main() -> int:
                    "visual tokens, T=0 (end-to-end, other hardware; not comparable)",
         "input_gen_s": round(t_gen, 1),
     }
+
+    # ---------------------------------------------------------------- other shapes, on request
+    if args.other_configs:
+        def time_verify(cfg_o, n_layers_o, n_q_o=None, parent_o=None):
+            """Verify attention per layer on `cfg_o`: distinct K/V per layer (token-major) so that
+            the Infinity Cache cannot serve the stream; graph replay, HIP events."""
+            kw = {} if n_q_o is None else {"n_q": n_q_o, "parent": parent_o}
+            cs = [wl.verify_case(cfg_o, args.seed, layer=l, **kw) for l in range(n_layers_o)]
+            c0 = cs[0]
+            ls = [(dev(c.q, bf16), dev(c.k, bf16), dev(c.v, bf16)) for c in cs]
+            par = None if c0.parent is None else dev(c0.parent)
+            nb = len(c0.cu_seqlens) - 1
+            tot = int(c0.cu_seqlens[-1])
+            wso = torch.empty(sp.verify_attn_workspace_bytes(*ls[0], nb, c0.n_q, tot),
+                              dtype=torch.uint8, device="cuda")
+            outs = [torch.empty_like(q) for q, _, _ in ls]
+
+            def run(passes):
+                for (q, k, v), o in zip(ls, outs):
+                    sp.verify_attn(q, k, v, c0.cu_seqlens, par, c0.n_q, out=o, want_lse=False,
+                                   workspace=wso, passes=passes)
+            us_all = time_graph(capture(lambda: run(3)), 30) / n_layers_o
+            us_part = time_graph(capture(lambda: run(1)), 30) / n_layers_o
+            g_ = cfg_o.n_q_heads // cfg_o.n_kv_heads
+            byts = 2 * tot * cfg_o.n_kv_heads * cfg_o.head_dim * 2 + 2 * c0.q.shape[0] * cfg_o.n_q_heads * cfg_o.head_dim * 2
+            return {"batch": nb, "tokens": tot, "n_q": int(c0.n_q), "rows_per_kv_head": int(c0.n_q) * g_,
+                    "verify_us_per_layer": round(us_all, 2), "partial_pass_us": round(us_part, 2),
+                    "algorithmic_gbps": round(byts / us_all * 1e-3, 1)}
+        other = {"C2": time_verify(wl.C2, 12), "C3": time_verify(wl.C3, 8), "C4": time_verify(wl.C4, 4)}
+        for name, nodes, br in (("tree_30_4_8", 30, (4, 3, 2, 2)), ("tree_48_5_10", 48, (5, 3, 2, 2, 1)),
+                                ("tree_16", 16, (4, 2, 1, 1))):
+            par_t = wl.pruned_tree(args.seed, nodes, br)
+            other[name + "_at_C3_context"] = time_verify(wl.C3, 8, len(par_t), par_t)
+        result["other_configs"] = other
 
     # ---------------------------------------------------------------- CPU oracle beside it
     if not args.no_cpu_baseline:
