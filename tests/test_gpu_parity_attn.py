@@ -94,6 +94,25 @@ def test_verify_context_lengths(sp, oracle, dtype, Hq, Hkv, d, L):
         _verify_and_check(sp, oracle, c, f"verify {dtype} {Hq}/{Hkv}/{d} L={L} n_q={n_q}")
 
 
+@pytest.mark.parametrize("lengths,n_q,nodes", [
+    ((3000, 3000, 3000), 4, 0),            # 19 splits each: one x range of 24 per (head, sequence)
+    ((5200, 4800), 8, 0),                  # 33 + 30 splits in x ranges of 40: padding, rotated XCD order
+    ((5000, 4300), 0, 19),                 # 16 + 14 splits, two row blocks of 128 (a tree of 19 nodes)
+    ((5200, 4100), 8, 0),                  # 33 + 26 splits: more than a quarter padding -> flat grid
+    ((5200, 3900), 0, 19),                 # flat grid with two row blocks
+    ((6000, 300, 40, 2500, 10), 5, 0),     # very ragged: flat grid, sequences of a single split
+])
+def test_verify_batches_cover_both_grid_shapes(sp, oracle, lengths, n_q, nodes):
+    """Batches of the matrix-core path (bf16, 28/4 heads, d = 128) in the launch shapes the host
+    chooses between: per-(head, sequence) x ranges, with and without padding, and the flat grid."""
+    cfg = _cfg("bf16", 28, 4, 128)
+    lay = tuple(((wl.TEXT, n),) for n in lengths)
+    parent = wl.pruned_tree(7, nodes, (4, 3, 2)) if nodes else None
+    c = wl.verify_case(cfg, seed=len(lengths) + n_q, layouts=lay,
+                       n_q=len(parent) if nodes else n_q, parent=parent)
+    _verify_and_check(sp, oracle, c, f"batch {lengths} n_q={c.n_q}")
+
+
 @pytest.mark.parametrize("dtype,Hq,Hkv,d", [("f32", 4, 1, 64), ("bf16", 28, 4, 128)])
 def test_verify_trees(sp, oracle, dtype, Hq, Hkv, d):
     cfg = _cfg(dtype, Hq, Hkv, d)
