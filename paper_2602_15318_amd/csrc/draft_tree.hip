@@ -1,8 +1,9 @@
 // Dynamic draft tree: top-k log-probabilities over the vocabulary, best-first level expansion,
 // final selection.  Everything after the lm_head GEMM is small (a few KB to a few MB), so the
 // kernels are written for few launches and short dependent chains, not for bandwidth:
-//   topk_chunk_kernel   grid (64 chunks, M rows): the chunk's k largest logits by k rounds of a
-//                       workgroup-wide argmax (a thread owns ~10 logits in registers);
+//   topk_chunk_kernel   grid (64 chunks, M rows): the chunk's softmax statistics and its k largest
+//                       logits (a thread owns ~10 logits in registers; k rounds of a per-wavefront
+//                       argmax, then a merge of the four wavefronts' lists);
 //   topk_merge_kernel   one wavefront per row: k rounds of a 64-lane argmax over the heads of the
 //                       chunk lists; the k best are written in order with their log-softmax from
 //                       the row's statistics;
@@ -25,10 +26,17 @@ __device__ __forceinline__ bool better(float va, int ia, float vb, int ib) {
   return va > vb || (va == vb && ia < ib);
 }
 
+// One workgroup of 4 wavefronts per (chunk of the vocabulary, row); a thread owns up to 16 logits
+// in registers.  The chunk's softmax statistics (max and sum of exp2 in the log2 domain) come from
+// the same registers.  Top k: every wavefront takes the k best of its own logits by k rounds of a
+// 64-lane argmax on the vector ALU (value by maximum, then the lowest index among the lanes that
+// hold it; no barrier, no LDS crossbar), then wavefront 0 merges the four sorted lists.
 __global__ void __launch_bounds__(kTopkThreads)
 topk_chunk_kernel(TopkArgs a) {
-  __shared__ float wv[kTopkThreads / 64];
-  __shared__ int wi[kTopkThreads / 64];
+  constexpr int kWaves = kTopkThreads / 64;
+  __shared__ float red[kWaves];
+  __shared__ float lv[kWaves][kTreeMaxWidth];
+  __shared__ int li[kWaves][kTreeMaxWidth];
   const int c = blockIdx.x, r = blockIdx.y;
   const int per = (a.V + kStatChunks - 1) / kStatChunks;
   const int v0 = min(a.V, c * per), v1 = min(a.V, v0 + per);
@@ -40,34 +48,65 @@ topk_chunk_kernel(TopkArgs a) {
     const int v = v0 + threadIdx.x + j * kTopkThreads;
     val[j] = v < v1 ? lg[v] : -INFINITY;
   }
+  // ---- statistics of the chunk (temperature 1): m = max of l log2 e, s = sum of exp2(l log2 e - m)
+  {
+    constexpr float kLog2e = 1.4426950408889634f;
+    float m = -INFINITY;
+#pragma unroll
+    for (int j = 0; j < kTopkPerThread; ++j) m = fmaxf(m, val[j]);
+    m = wave_max_valu(m);
+    if (lane == 0) red[w] = m;
+    __syncthreads();
+    m = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+    __syncthreads();
+    const float ms = v1 > v0 ? m * kLog2e : kNegBig;       // an empty chunk: (kNegBig, 0)
+    float s = 0.f;
+#pragma unroll
+    for (int j = 0; j < kTopkPerThread; ++j) s += fast_exp2(fmaf(val[j], kLog2e, -ms));   // exp2(-inf) = 0
+    s = wave_sum_valu(s);
+    if (lane == 0) red[w] = s;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      float *o = a.stats + ((int64_t)r * kStatChunks + c) * 2;
+      o[0] = ms;
+      o[1] = v1 > v0 ? red[0] + red[1] + red[2] + red[3] : 0.f;
+    }
+  }
+  // ---- the wavefront's k best, in decreasing order (ties: lower index first)
   for (int round = 0; round < a.k; ++round) {
     float bv = -INFINITY;
-    int bi = 0x7fffffff;
-#pragma unroll
-    for (int j = 0; j < kTopkPerThread; ++j) {
-      const int v = v0 + threadIdx.x + j * kTopkThreads;
-      if (v < v1 && better(val[j], v, bv, bi)) { bv = val[j]; bi = v; }
-    }
-#pragma unroll
-    for (int o = 32; o >= 1; o >>= 1) {
-      const float ov = __shfl_xor(bv, o, 64);
-      const int oi = __shfl_xor(bi, o, 64);
-      if (better(ov, oi, bv, bi)) { bv = ov; bi = oi; }
-    }
-    if (lane == 0) { wv[w] = bv; wi[w] = bi; }
-    __syncthreads();
-#pragma unroll
-    for (int k = 0; k < kTopkThreads / 64; ++k)
-      if (better(wv[k], wi[k], bv, bi)) { bv = wv[k]; bi = wi[k]; }
-    __syncthreads();
-    // the winner leaves its owner's registers (an exhausted chunk yields -inf / 0x7fffffff)
+    int bj = 0;
 #pragma unroll
     for (int j = 0; j < kTopkPerThread; ++j)
-      if (v0 + (int)threadIdx.x + j * kTopkThreads == bi) val[j] = -INFINITY;
-    if (threadIdx.x == 0) {
-      const int64_t o = ((int64_t)r * kStatChunks + c) * a.k + round;
-      a.cand_val[o] = bi == 0x7fffffff ? -INFINITY : bv;
-      a.cand_idx[o] = bi;
+      if (val[j] > bv) { bv = val[j]; bj = j; }             // ascending index: the lowest wins a tie
+    const float wv = wave_max_valu(bv);
+    const int bi = v0 + (int)threadIdx.x + bj * kTopkThreads;
+    const int wi = wave_min_valu((bv == wv && bv > -INFINITY) ? bi : 0x7fffffff);
+    // the winner leaves its owner's registers (an exhausted wavefront yields -inf / 0x7fffffff)
+#pragma unroll
+    for (int j = 0; j < kTopkPerThread; ++j)
+      if (j == bj && bi == wi) val[j] = -INFINITY;
+    if (lane == 0) { lv[w][round] = wi == 0x7fffffff ? -INFINITY : wv; li[w][round] = wi; }
+  }
+  __syncthreads();
+  // ---- merge of the four lists: lane l < 4 walks list l, every round the best head wins
+  if (w == 0) {
+    int pos = 0;
+    float hv = lane < kWaves ? lv[lane][0] : -INFINITY;
+    int hi = lane < kWaves ? li[lane][0] : 0x7fffffff;
+    for (int round = 0; round < a.k; ++round) {
+      const float wv = wave_max_valu(hv);
+      const int wi = wave_min_valu((hv == wv && hi != 0x7fffffff) ? hi : 0x7fffffff);
+      if (lane == 0) {
+        const int64_t o = ((int64_t)r * kStatChunks + c) * a.k + round;
+        a.cand_val[o] = wi == 0x7fffffff ? -INFINITY : wv;
+        a.cand_idx[o] = wi;
+      }
+      if (hi == wi && wi != 0x7fffffff) {                   // the owner of the winner moves on
+        ++pos;
+        hv = pos < a.k ? lv[lane][pos] : -INFINITY;
+        hi = pos < a.k ? li[lane][pos] : 0x7fffffff;
+      }
     }
   }
 }
@@ -79,29 +118,35 @@ topk_merge_kernel(TopkArgs a) {
   const int r = blockIdx.x, lane = threadIdx.x;
   const float pm = a.stats[((int64_t)r * kStatChunks + lane) * 2];
   const float ps = a.stats[((int64_t)r * kStatChunks + lane) * 2 + 1];
-  const float m = wave_max(pm);
-  const float Z = wave_sum(ps * fast_exp2(pm - m));
-  const float lse = (m + fast_log2(Z)) * kLn2;       // m is in the log2 domain (l log2 e)
+  // the lane's whole list goes to LDS first (all loads in flight at once: one round trip); the
+  // walk then costs an LDS read per round instead of a dependent global load
+  __shared__ float sv[kTreeMaxWidth][64];
+  __shared__ int si[kTreeMaxWidth][64];
   const float *cv = a.cand_val + ((int64_t)r * kStatChunks + lane) * a.k;
   const int32_t *ci = a.cand_idx + ((int64_t)r * kStatChunks + lane) * a.k;
-  int pos = 0;
-  float hv = cv[0];
-  int hi = ci[0];
-  for (int round = 0; round < a.k; ++round) {
-    float bv = hv;
-    int bi = hi;
 #pragma unroll
-    for (int o = 32; o >= 1; o >>= 1) {
-      const float ov = __shfl_xor(bv, o, 64);
-      const int oi = __shfl_xor(bi, o, 64);
-      if (better(ov, oi, bv, bi)) { bv = ov; bi = oi; }
+  for (int j = 0; j < kTreeMaxWidth; ++j) {
+    sv[j][lane] = j < a.k ? cv[j] : -INFINITY;
+    si[j][lane] = j < a.k ? ci[j] : 0x7fffffff;
+  }
+  const float m = wave_max_valu(pm);
+  const float Z = wave_sum_valu(ps * fast_exp2(pm - m));
+  const float lse = (m + fast_log2(Z)) * kLn2;       // m is in the log2 domain (l log2 e)
+  int pos = 0;
+  float hv = sv[0][lane];                            // (a lane reads only what it wrote itself)
+  int hi = si[0][lane];
+  for (int round = 0; round < a.k; ++round) {
+    const float wv = wave_max_valu(hv);
+    const int wi = wave_min_valu((hv == wv && hi != 0x7fffffff) ? hi : 0x7fffffff);
+    if (wi == 0x7fffffff) break;                     // every list exhausted (uniform)
+    if (lane == 0) {
+      a.ids[(int64_t)r * a.k + round] = wi;
+      a.logp[(int64_t)r * a.k + round] = wv - lse;
     }
-    if (hi == bi && bi != 0x7fffffff) {              // the owner of the winner moves on
-      a.ids[(int64_t)r * a.k + round] = bi;
-      a.logp[(int64_t)r * a.k + round] = bv - lse;
+    if (hi == wi) {                                  // the owner of the winner moves on
       ++pos;
-      hv = pos < a.k ? cv[pos] : -INFINITY;
-      hi = pos < a.k ? ci[pos] : 0x7fffffff;
+      hv = pos < a.k ? sv[pos][lane] : -INFINITY;
+      hi = pos < a.k ? si[pos][lane] : 0x7fffffff;
     }
   }
 }

@@ -14,7 +14,8 @@ constexpr int kTreeMaxPool = 2048;      // width + (depth - 1) * width^2 must fi
 
 struct TopkArgs {
   const float *logits;      // [M, V]
-  const float *stats;       // [M, kStatChunks, 2] (max, sum of exp2) in the log2 domain, T = 1
+  float *stats;             // [M, kStatChunks, 2] (max, sum of exp2) in the log2 domain, T = 1:
+                            // written by the chunk kernel, read by the merge kernel
   float *cand_val;          // [M, kStatChunks, k] chunk-local top-k (decreasing)
   int32_t *cand_idx;
   int32_t *ids;             // [M, k]

@@ -583,16 +583,8 @@ int sparrow_draft_topk(int32_t dtype, const void *hidden_rows, const void *lm_he
   hipStream_t st = (hipStream_t)hip_stream;
   hipError_t e = mfma ? launch_lm_head_mfma(a, st) : launch_lm_head_generic(dtype, a, st);
   if (e != hipSuccess) return fail(SPARROW_ERR_DEVICE, "lm_head launch: %s", hipGetErrorString(e));
-  SampleArgs s;
-  memset(&s, 0, sizeof(s));
-  s.logits = a.logits;
-  s.stats = (float *)(ws + base + lb);
-  s.blk_sum = (float *)(ws + base + lb + sb);
-  s.M = M; s.V = vocab; s.inv_temp_log2 = 1.4426950408889634f;
-  e = launch_logit_stats(s, st);
-  if (e != hipSuccess) return fail(SPARROW_ERR_DEVICE, "logit statistics launch: %s", hipGetErrorString(e));
   TopkArgs t;
-  t.logits = a.logits; t.stats = s.stats;
+  t.logits = a.logits; t.stats = (float *)(ws + base + lb);      // written by the chunk kernel
   t.cand_val = (float *)(ws + base + extra);
   t.cand_idx = (int32_t *)(ws + base + extra + topk_cand_bytes(M, k));
   t.ids = ids; t.logp = logp; t.M = M; t.V = vocab; t.k = k;
