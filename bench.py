@@ -8,7 +8,12 @@ greedy acceptance (lm_head 152,064 x 3584 on 9 rows, argmax, longest accepted pr
 bf16 with synthetic seeded inputs already resident in HBM.  The step is captured once in a HIP
 graph and replayed, so the timed region holds GPU work only.
 
-Prints ONE JSON line (see README for the fields).
+Prints ONE JSON line: `value` is the step's algorithmic bytes over its time; `roofline` describes
+the dominant kernel (the split-context partial pass of verification attention: algorithmic bytes
+per launch over its average launch duration from HIP events, against the published HBM peak, with
+the HBM traffic read from the committed rocprofv3 counter summary and the time of a plain read of
+the same bytes beside it); `cpu_baseline` is the fp64 CPU oracle timed on one whole step.  The
+other fields time the parts of the step and the neighbouring steps of the method on their own.
 """
 from __future__ import annotations
 
