@@ -24,7 +24,9 @@
  *    kernels on `hip_stream` (a hipStream_t passed as void*, NULL = the default
  *    stream) and returns without synchronising.  Host arrays are fully read
  *    before the call returns.  Device buffers must stay valid until the
- *    stream has passed the enqueued work.  Calls are graph-capturable.
+ *    stream has passed the enqueued work.  Calls are graph-capturable; the
+ *    first call of an entry point in a process may do one-time set-up of its
+ *    kernels (raising their LDS limit), so make one call outside capture first.
  *  - Errors: every entry point returns a sparrow_status (0 = ok, negative =
  *    error); on error nothing has been enqueued and sparrow_last_error()
  *    describes the reason.  Contents of device arrays (text_idx ascending and
