@@ -24,34 +24,67 @@ constexpr int kWalkThreads = 1024;
 constexpr int kBonusBlock = 256;              // tokens per block of the bonus draw
 constexpr int kBonusMaxBlocks = kSampleMaxVocab / kBonusBlock;
 
+// A wavefront owns whole blocks of 256 tokens (blocks b0 + w, b0 + w + 4, ... of the chunk), a lane
+// four consecutive tokens of each: the chunk is read once, 16 bytes per lane, and stays in
+// registers for the maximum and for the sums.
+constexpr int kStatBlocksPerWave = kBonusMaxBlocks / kStatChunks / (kStatThreads / 64);   // 16
+
 __global__ void __launch_bounds__(kStatThreads)
 logit_stats_kernel(SampleArgs a) {
   __shared__ float red[kStatThreads / 64];
+  constexpr int kWaves = kStatThreads / 64;
   const int c = blockIdx.x, r = blockIdx.y;
   const int n_blk = (a.V + kBonusBlock - 1) / kBonusBlock;
   const int bpc = (n_blk + kStatChunks - 1) / kStatChunks;          // blocks per chunk
   const int b0 = min(n_blk, c * bpc), b1 = min(n_blk, b0 + bpc);
-  const int v0 = b0 * kBonusBlock, v1 = min(a.V, b1 * kBonusBlock);
   const float *lg = a.logits + (int64_t)r * a.V;
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  // scaled logits of this lane: x[k][i] = token (b0 + w + 4 k) * 256 + 4 lane + i, kNegBig past V
+  float x[kStatBlocksPerWave][4];
+  const bool row_aligned = (((int64_t)r * a.V) & 3) == 0;           // 16-byte loads possible
+#pragma unroll
+  for (int k = 0; k < kStatBlocksPerWave; ++k) {
+    const int ib = b0 + w + kWaves * k;
+    const int v = ib * kBonusBlock + 4 * lane;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) x[k][i] = kNegBig;
+    if (ib < b1) {
+      if (row_aligned && v + 3 < a.V) {
+        const f32x4 q = *reinterpret_cast<const f32x4 *>(lg + v);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) x[k][i] = q[i] * a.inv_temp_log2;
+      } else {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+          if (v + i < a.V) x[k][i] = lg[v + i] * a.inv_temp_log2;
+      }
+    }
+  }
   float m = kNegBig;
-  for (int v = v0 + threadIdx.x; v < v1; v += kStatThreads) m = fmaxf(m, lg[v] * a.inv_temp_log2);
-  m = wave_max(m);
+#pragma unroll
+  for (int k = 0; k < kStatBlocksPerWave; ++k)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) m = fmaxf(m, x[k][i]);
+  m = wave_max_valu(m);
   if (lane == 0) red[w] = m;
   __syncthreads();
   m = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
   __syncthreads();
-  // block sums relative to the chunk's max (a wavefront per block, a lane reads 4 tokens)
+  // block sums relative to the chunk's max
   float s = 0.f;
-  for (int ib = b0 + w; ib < b1; ib += kStatThreads / 64) {
-    const int v = ib * kBonusBlock + 4 * lane;
-    float t = 0.f;
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
-      if (v + i < a.V) t += fast_exp2(lg[v + i] * a.inv_temp_log2 - m);
-    t = wave_sum_valu(t);
-    if (lane == 0) a.blk_sum[(int64_t)r * n_blk + ib] = t;
-    s += t;                                   // the same value in every lane
+  for (int k = 0; k < kStatBlocksPerWave; ++k) {
+    const int ib = b0 + w + kWaves * k;
+    if (ib < b1) {                              // uniform over the wavefront
+      const int v = ib * kBonusBlock + 4 * lane;
+      float t = 0.f;
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+        if (v + i < a.V) t += fast_exp2(x[k][i] - m);
+      t = wave_sum_valu(t);
+      if (lane == 0) a.blk_sum[(int64_t)r * n_blk + ib] = t;
+      s += t;                                   // the same value in every lane
+    }
   }
   if (lane == 0) red[w] = s;
   __syncthreads();
