@@ -286,6 +286,25 @@ def main() -> int:
             if line.startswith("traffic_bytes_per_launch:"):
                 traffic = int(float(line.split(":")[1]))
 
+    # the same kernels on a batch: the 28 layers' K/V handed over as 28 sequences of one call (what
+    # one layer of a 28-request decode batch at this context looks like); not part of `value`
+    nb = cfg.n_layers
+    kb = torch.cat([k.permute(1, 0, 2) for _, k, _ in layers], dim=1).permute(1, 0, 2)   # head-major
+    vb = torch.cat([v.permute(1, 0, 2) for _, _, v in layers], dim=1).permute(1, 0, 2)
+    qb = torch.cat([q for q, _, _ in layers], dim=0)
+    cu_b = (np.arange(nb + 1, dtype=np.int64) * T).astype(np.int32)
+    ws_b = torch.empty(sp.verify_attn_workspace_bytes(qb, kb, vb, nb, n_q, nb * T), dtype=torch.uint8,
+                       device="cuda")
+    out_b = torch.empty_like(qb)
+    def verify_batch(passes=3):
+        sp.verify_attn(qb, kb, vb, cu_b, None, n_q, out=out_b, want_lse=False, workspace=ws_b,
+                       passes=passes)
+    us_batch = time_graph(capture(verify_batch), 20)
+    us_batch_partial = time_graph(capture(lambda: verify_batch(1)), 20)
+    # (different split boundaries than the per-layer calls: equal up to rounding, not bit for bit)
+    batch_diff = float((out_b.view(nb, -1).float() - torch.stack([o.view(-1) for o in v_out]).float()).abs().max())
+    del kb, vb
+
     result = {
         "metric": "verify-attn HBM GB/s at 25k ctx over the full verify step "
                   "(28-layer verify attention + draft window attention + lm_head/argmax/accept)",
@@ -315,6 +334,13 @@ def main() -> int:
                         "draft_qkv_append_us": round(us_qkv, 2),
                         "draft_qkv_append_gbps": round(bytes_qkv / us_qkv * 1e-3, 1)},
         "kv_commit_us": round(us_commit, 2),
+        "verify_attn_batch_of_28": {
+            "note": "one call on 28 sequences of 26,112 context (the 28 layers' K/V as a batch): the "
+                    "launch, fill and tail of the kernels are paid once for 1.5 GB; not in `value`",
+            "us": round(us_batch, 1), "partial_pass_us": round(us_batch_partial, 1),
+            "gbps": round((cfg.n_layers * bytes_verify_layer) / us_batch * 1e-3, 1),
+            "pct_hbm_peak": round((cfg.n_layers * bytes_verify_layer) / us_batch * 1e-3 / HBM_PEAK_GBPS * 100, 2),
+            "max_abs_diff_to_per_layer_calls": round(batch_diff, 6)},
         "accept_sample_t1_us": round(us_accept_sample, 2),
         "draft_tree_30_4_8": {"draft_topk_8rows_us": round(us_topk, 2),
                               "expand_plus_select_us": round(us_tree_tail, 2)},

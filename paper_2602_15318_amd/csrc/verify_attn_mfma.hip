@@ -17,6 +17,7 @@
 //   O^T += V^T P^T  B = P^T straight from the score registers (k index = the lane's own eight
 //                 tokens), A = V^T through the transposing LDS read ds_read_b64_tr_b16.
 // The online-softmax state (m, l) and the rescale factor are per lane (= per query row).
+#include <algorithm>
 #include <type_traits>
 
 #include "common.hpp"
@@ -460,8 +461,11 @@ verify_partial_mfma_kernel(VerifyArgs a, SeqTable tab, PieceTable pt, int rbs, i
 // with 4 wavefronts x 16 splits and two d-tiles per workgroup 20.6 us, one d-tile 19.0 us, 8 x 8
 // 18.7 us, 16 x 4 18.5 us.
 constexpr int kCombInFlight = 4;
-constexpr int kCombWaves = 16;
 
+// kCombWaves = 16 for the decode-time case (one sequence cut into ~64 splits); 4 when no sequence
+// of the call has more than 16 splits (batches), where 16 wavefronts per output tile would mostly
+// find nothing to merge.
+template <int kCombWaves>
 __global__ void __launch_bounds__(64 * kCombWaves)
 verify_combine_tiled_kernel(VerifyArgs a, SeqTable tab, int rbs, int g) {
   __shared__ f32x4 xo[kCombWaves][64];
@@ -584,8 +588,12 @@ hipError_t launch_verify_combine_mfma(const VerifyArgs &a, const SeqTable &tab, 
   const int R = a.n_q * (a.Hq / a.Hkv);
   const int rbs = (R + kRowsPerWG - 1) / kRowsPerWG;
   dim3 grid(a.Hkv * rbs * 4, 8, a.B);
-  hipLaunchKernelGGL(verify_combine_tiled_kernel, grid, dim3(64 * kCombWaves), 0, st, a, tab, rbs,
-                     a.Hq / a.Hkv);
+  int max_ns = 0;
+  for (int b = 0; b < a.B; ++b) max_ns = std::max(max_ns, tab.cu_split[b + 1] - tab.cu_split[b]);
+  if (max_ns > 16)
+    hipLaunchKernelGGL(verify_combine_tiled_kernel<16>, grid, dim3(64 * 16), 0, st, a, tab, rbs, a.Hq / a.Hkv);
+  else
+    hipLaunchKernelGGL(verify_combine_tiled_kernel<4>, grid, dim3(64 * 4), 0, st, a, tab, rbs, a.Hq / a.Hkv);
   return hipGetLastError();
 }
 
