@@ -174,27 +174,35 @@ def test_strided_kv_and_explicit_scale(sp, oracle):
     check_attn(host(out), ref, "bf16", "strided kv")
 
 
-def test_head_major_kv_layout(sp, oracle):
+@pytest.mark.parametrize("interleaved", [False, True])
+def test_head_major_kv_layout(sp, oracle, interleaved):
     """K/V stored [Hkv, T, d] (a head's tokens contiguous) and passed as a [T, Hkv, d] view: same
     results as the token-major layout, for the verification and the draft attention, chain and
-    tree, matrix-core and plain-ALU kernels."""
+    tree, matrix-core and plain-ALU kernels.  Interleaved: one [Hkv, T, 2, d] allocation, a token's
+    K row followed by its V row (k and v are views into it with a token stride of 2 d)."""
     import torch
     for dtype, Hq, Hkv, d in (("bf16", 28, 4, 128), ("f32", 4, 2, 64)):
         cfg = _cfg(dtype, Hq, Hkv, d)
         lay = (((wl.TEXT, 50), (wl.VISUAL, 1100), (wl.TEXT, 77)), ((wl.VISUAL, 300), (wl.TEXT, 45)))
+
+        def hm_pair(kh, vh):
+            if not interleaved:
+                hm = lambda x: dev(x, dtype).permute(1, 0, 2).contiguous().permute(1, 0, 2)   # noqa: E731
+                return hm(kh), hm(vh)
+            kv = torch.stack([dev(kh, dtype).permute(1, 0, 2), dev(vh, dtype).permute(1, 0, 2)], dim=2).contiguous()
+            return kv[:, :, 0, :].permute(1, 0, 2), kv[:, :, 1, :].permute(1, 0, 2)
         for parent in (None, wl.pruned_tree(1, 25, (4, 2, 2, 1, 1))):
             n_q = 6 if parent is None else len(parent)
             c = wl.verify_case(cfg, seed=77, layouts=lay, n_q=n_q, parent=parent)
-            hm = lambda x: dev(x, dtype).permute(1, 0, 2).contiguous().permute(1, 0, 2)   # noqa: E731
-            k, v = hm(c.k), hm(c.v)
-            assert k.stride(1) > k.stride(0)
+            k, v = hm_pair(c.k, c.v)
+            assert k.stride(1) > k.stride(0) and k.stride(0) == (2 * d if interleaved else d)
             par = None if parent is None else dev(parent)
             out, lse = sp.verify_attn(dev(c.q, dtype), k, v, c.cu_seqlens, par, n_q)
             torch.cuda.synchronize()
             ref, ref_lse = oracle.verify_attn(c.q, c.k, c.v, c.cu_seqlens, parent, n_q)
             check_attn(host(out), ref, dtype, f"head-major verify {dtype} n_q={n_q}")
         dc = wl.draft_case(cfg, seed=78, layouts=lay)
-        k, v = hm(dc.k), hm(dc.v)
+        k, v = hm_pair(dc.k, dc.v)
         out, _ = sp.draft_window_attn(dev(dc.q, dtype), k, v, dc.cu_seqlens, dev(dc.text_idx), dc.cu_text,
                                       dc.window)
         torch.cuda.synchronize()
