@@ -113,6 +113,29 @@ def test_verify_batches_cover_both_grid_shapes(sp, oracle, lengths, n_q, nodes):
     _verify_and_check(sp, oracle, c, f"batch {lengths} n_q={c.n_q}")
 
 
+@pytest.mark.parametrize("seed", range(10))
+def test_verify_random_batches(sp, oracle, seed):
+    """Seeded random batches on the matrix-core path: 1-7 sequences of 1-4000 context tokens
+    (text and visual runs mixed), a chain or a random tree of 1-40 rows, 28/4 or 32/8 heads."""
+    rng = np.random.default_rng(9000 + seed)
+    Hq, Hkv = ((28, 4), (32, 8))[seed % 2]
+    cfg = _cfg("bf16", Hq, Hkv, 128)
+    B = int(rng.integers(1, 8))
+    lay = []
+    for _ in range(B):
+        n = int(rng.integers(1, 4001)) if rng.random() < 0.8 else int(rng.integers(1, 40))
+        cut = int(rng.integers(0, n + 1))
+        lay.append(tuple(seg for seg in ((wl.VISUAL, cut), (wl.TEXT, n - cut)) if seg[1] > 0))
+    if rng.random() < 0.5:
+        n_q, parent = int(rng.integers(1, 17)), None
+    else:
+        nodes = int(rng.integers(2, 41))
+        parent = wl.pruned_tree(seed, nodes, (4, 3, 2, 2, 1, 1))
+        n_q = len(parent)
+    c = wl.verify_case(cfg, seed=seed, layouts=tuple(lay), n_q=n_q, parent=parent)
+    _verify_and_check(sp, oracle, c, f"random batch {seed}: B={B} n_q={n_q} tree={parent is not None}")
+
+
 @pytest.mark.parametrize("dtype,Hq,Hkv,d", [("f32", 4, 1, 64), ("bf16", 28, 4, 128)])
 def test_verify_trees(sp, oracle, dtype, Hq, Hkv, d):
     cfg = _cfg(dtype, Hq, Hkv, d)
