@@ -97,33 +97,44 @@ __global__ void __launch_bounds__(1024) accept_finalize_kernel(AcceptArgs a) {
     dr_s[tid] = a.draft_ids[tid];
     par_s[tid] = a.parent ? a.parent[j] : j - 1;
   }
-  for (int r = w; r < a.M; r += 16) {
-    float bv = -INFINITY;
-    int bi = 0x7fffffff;
-    const float *cv = a.cand_val + (int64_t)r * a.n_cand;
-    const int32_t *ci = a.cand_idx + (int64_t)r * a.n_cand;
-    constexpr int kU = 16;                               // independent loads in flight per lane
-    for (int c0 = lane; c0 < a.n_cand; c0 += 64 * kU) {
-      float v[kU];
-      int i[kU];
+  // two rows per wavefront at a time (rows r and r + 16): their candidate loads are in flight
+  // together, and the 64-lane argmax runs on the vector ALU (maximum, then the lowest index
+  // among the lanes that hold it)
+  constexpr int kU = 16;                                 // independent loads in flight per lane and row
+  for (int r0 = w; r0 < a.M; r0 += 32) {
+    float bv[2];
+    int bi[2];
 #pragma unroll
-      for (int u = 0; u < kU; ++u) {
-        const int c = c0 + 64 * u;
-        const bool in = c < a.n_cand;
-        v[u] = in ? cv[c] : -INFINITY;
-        i[u] = in ? ci[c] : 0x7fffffff;
+    for (int h = 0; h < 2; ++h) { bv[h] = -INFINITY; bi[h] = 0x7fffffff; }
+    for (int c0 = lane; c0 < a.n_cand; c0 += 64 * kU) {
+      float v[2][kU];
+      int i[2][kU];
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        const int r = min(r0 + 16 * h, a.M - 1);         // the second row may not exist: a valid duplicate
+        const float *cv = a.cand_val + (int64_t)r * a.n_cand;
+        const int32_t *ci = a.cand_idx + (int64_t)r * a.n_cand;
+#pragma unroll
+        for (int u = 0; u < kU; ++u) {
+          const int c = c0 + 64 * u;
+          const bool in = c < a.n_cand;
+          v[h][u] = in ? cv[c] : -INFINITY;
+          i[h][u] = in ? ci[c] : 0x7fffffff;
+        }
       }
 #pragma unroll
-      for (int u = 0; u < kU; ++u)
-        if (v[u] > bv || (v[u] == bv && i[u] < bi)) { bv = v[u]; bi = i[u]; }
+      for (int h = 0; h < 2; ++h)
+#pragma unroll
+        for (int u = 0; u < kU; ++u)
+          if (v[h][u] > bv[h] || (v[h][u] == bv[h] && i[h][u] < bi[h])) { bv[h] = v[h][u]; bi[h] = i[h][u]; }
     }
 #pragma unroll
-    for (int o = 32; o >= 1; o >>= 1) {
-      const float ov = __shfl_xor(bv, o, 64);
-      const int oi = __shfl_xor(bi, o, 64);
-      if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
+    for (int h = 0; h < 2; ++h) {
+      const int r = r0 + 16 * h;
+      const float wv = wave_max_valu(bv[h]);
+      const int wi = wave_min_valu(bv[h] == wv ? bi[h] : 0x7fffffff);
+      if (lane == 0 && r < a.M) { tgt[r] = wi; a.target_ids[r] = wi; }
     }
-    if (lane == 0) { tgt[r] = bi; a.target_ids[r] = bi; }
   }
   __syncthreads();
   if (tid < a.B) {

@@ -132,9 +132,19 @@ constexpr int kKsGroup = 4;               // vocabulary tiles (of 16 rows) per g
 
 // NB = blocks of 16 hidden rows handled in one pass over W (1 or 2); the vocabulary group is
 // kKsGroup / NB tiles so that the partial logits held in registers stay at 16 per lane.
+// halves = 2 (33 to 64 hidden rows): ONE pass over W for two blocks of 32 rows.  The workgroups
+// form pairs that stream the same vocabulary tiles, one for rows row0 .. row0+31, the other for
+// rows row0+32 .. row0+63; the two of a pair have indices 8 apart, i.e. they run at the same time
+// on the same XCD (workgroups are handed to the 8 XCDs round-robin), so the second fetch of a
+// weight tile is served by that XCD's L2 and HBM still sees the weights once.  (Only the speed
+// depends on that placement.)
 template <int NW, int NB>
 __global__ void __launch_bounds__(NW * 64)
-lm_head_ksplit_kernel(AcceptArgs a, int row0) {
+lm_head_ksplit_kernel(AcceptArgs a, int row0_arg, int halves) {
+  const int half = halves == 2 ? ((int)blockIdx.x >> 3) & 1 : 0;
+  const int wg = halves == 2 ? ((int)blockIdx.x >> 4) * 8 + ((int)blockIdx.x & 7) : (int)blockIdx.x;
+  const int n_wg = (int)gridDim.x / halves;            // streams of vocabulary tiles
+  const int row0 = row0_arg + 32 * half;
   constexpr int G = kKsGroup / NB;          // vocabulary tiles per group
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   // [NW][16 KB] staging, then [NW][G][64] f32x4 partial logits
@@ -152,10 +162,10 @@ lm_head_ksplit_kernel(AcceptArgs a, int row0) {
   // its slowest workgroup); a workgroup still reduces its tiles in groups of G, the last group
   // possibly short.
   const int n_vt = (V + 15) / 16;
-  const int n_tiles = n_vt > (int)blockIdx.x ? (n_vt - blockIdx.x + gridDim.x - 1) / gridDim.x : 0;
+  const int n_tiles = n_vt > wg ? (n_vt - wg + n_wg - 1) / n_wg : 0;
 
   // tile t of this workgroup -> first vocabulary row
-  auto tile_row0 = [&](int t) { return (blockIdx.x + t * gridDim.x) * 16; };
+  auto tile_row0 = [&](int t) { return (wg + t * n_wg) * 16; };
   // 16 loads of 1 KB: load r = the k-slice of row r of the tile (rows clamped to the last row).
   // Issued unconditionally (tile index clamped) so that the number of loads in flight is static.
   u32x4 buf[16];
@@ -175,13 +185,13 @@ lm_head_ksplit_kernel(AcceptArgs a, int row0) {
   for (int nb = 0; nb < NB; ++nb) {
     const int row = row0 + 16 * nb + n;
     const bool ok = row < a.M;
-    const bf16_t *hp = (const bf16_t *)a.hidden + (int64_t)(ok ? row : 0) * H + 512 * w + 8 * c4;
+    // Rows past M (padding of the last block) take the data of valid rows, row % M: their results
+    // are never stored, and every lane then fetches a row of its own -- the paired workgroups of
+    // the 33-to-64-row pass keep in step only if their prologues take the same time (with all
+    // padding lanes on one row the pass took 330 us at 33 rows, with this 229 us)
+    const bf16_t *hp = (const bf16_t *)a.hidden + (int64_t)(ok ? row : row % a.M) * H + 512 * w + 8 * c4;
 #pragma unroll
-    for (int ks = 0; ks < 16; ++ks) {
-      u32x4 v = *(const u32x4 *)(hp + 32 * ks);
-      if (!ok) v = (u32x4){0u, 0u, 0u, 0u};
-      hreg[nb][ks] = __builtin_bit_cast(bf16x8, v);
-    }
+    for (int ks = 0; ks < 16; ++ks) hreg[nb][ks] = __builtin_bit_cast(bf16x8, *(const u32x4 *)(hp + 32 * ks));
   }
 
   // staging: lane i of load r holds chunk i (16 bytes) of row r; stored at chunk position
@@ -191,12 +201,6 @@ lm_head_ksplit_kernel(AcceptArgs a, int row0) {
   int best_i[NB];
 #pragma unroll
   for (int nb = 0; nb < NB; ++nb) { best[nb] = -INFINITY; best_i[nb] = 0x7fffffff; }
-  f32x4 part[G][NB];
-#pragma unroll
-  for (int gg = 0; gg < G; ++gg)
-#pragma unroll
-    for (int nb = 0; nb < NB; ++nb) part[gg][nb] = (f32x4){0.f, 0.f, 0.f, 0.f};
-
   for (int t = 0; t < n_tiles; ++t) {
 #pragma unroll
     for (int r = 0; r < 16; ++r)
@@ -220,26 +224,21 @@ lm_head_ksplit_kernel(AcceptArgs a, int row0) {
       }
     }
     const int g = t % G;
-    // static register index for part[]
+    // the tile's partial logits go to LDS at once ([row block][wavefront][tile of the group]: G * NB
+    // = 4 slots per wavefront whatever NB), not into registers held for the whole group
 #pragma unroll
-    for (int gg = 0; gg < G; ++gg)
-      if (gg == g) {
-#pragma unroll
-        for (int nb = 0; nb < NB; ++nb) part[gg][nb] = acc[nb][0] + acc[nb][1];
-      }
+    for (int nb = 0; nb < NB; ++nb) red[((nb * NW + w) * G + g) * 64 + lane] = acc[nb][0] + acc[nb][1];
     if (g == G - 1 || t == n_tiles - 1) {     // uniform over the workgroup
-      // sum the group's partial logits over the wavefronts, one block of hidden rows at a time;
-      // wavefront w <= g takes tile w of the group (the last group may hold fewer than G tiles)
+      // sum the group's partial logits over the wavefronts; wavefront w <= g takes tile w of the
+      // group (the last group may hold fewer than G tiles)
+      __syncthreads();
+      if (w <= g) {
+        const int vbase = tile_row0(t - g + w) + 4 * c4;
 #pragma unroll
-      for (int nb = 0; nb < NB; ++nb) {
+        for (int nb = 0; nb < NB; ++nb) {
+          f32x4 sum = red[((nb * NW + 0) * G + w) * 64 + lane];
 #pragma unroll
-        for (int gg = 0; gg < G; ++gg) red[(w * G + gg) * 64 + lane] = part[gg][nb];
-        __syncthreads();
-        if (w <= g) {
-          f32x4 sum = red[(0 * G + w) * 64 + lane];
-#pragma unroll
-          for (int ww = 1; ww < NW; ++ww) sum += red[(ww * G + w) * 64 + lane];
-          const int vbase = tile_row0(t - g + w) + 4 * c4;
+          for (int ww = 1; ww < NW; ++ww) sum += red[((nb * NW + ww) * G + w) * 64 + lane];
 #pragma unroll
           for (int i = 0; i < 4; ++i)
             if (vbase + i < V && sum[i] > best[nb]) { best[nb] = sum[i]; best_i[nb] = vbase + i; }
@@ -250,11 +249,23 @@ lm_head_ksplit_kernel(AcceptArgs a, int row0) {
               if (vbase + i < V && row < a.M) a.logits[(int64_t)row * V + vbase + i] = sum[i];
           }
         }
-        __syncthreads();   // reads done before the next partials are written
       }
+      __syncthreads();   // reads done before the next partials are written
     }
   }
 
+  // a pair's workgroup leaves neutral candidates for the rows of the other half in its slots
+  if (halves == 2) {
+    const int other0 = row0_arg + 32 * (1 - half);
+    for (int e = tid; e < 32 * kKsGroup; e += NW * 64) {
+      const int row = other0 + e / kKsGroup;
+      if (row < a.M) {
+        const int slot = blockIdx.x * kKsGroup + e % kKsGroup;
+        a.cand_val[(int64_t)row * a.n_cand + slot] = -INFINITY;
+        a.cand_idx[(int64_t)row * a.n_cand + slot] = 0x7fffffff;
+      }
+    }
+  }
   // candidates: wavefronts 0..G-1 hold, per lane, the best of tiles g = w over all groups; the
   // workgroup always fills kKsGroup candidate slots (the others stay at -inf)
   if (w < kKsGroup) {
@@ -279,21 +290,23 @@ lm_head_ksplit_kernel(AcceptArgs a, int row0) {
 }
 
 template <int NW, int NB>
-hipError_t launch_ksplit_nb(const AcceptArgs &a, int row0, hipStream_t st) {
+hipError_t launch_ksplit_nb(const AcceptArgs &a, int row0, int halves, hipStream_t st) {
   const int lds = NW * 16384 + NW * kKsGroup * 64 * 16;
   static const hipError_t attr = hipFuncSetAttribute(
       (const void *)lm_head_ksplit_kernel<NW, NB>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
   if (attr != hipSuccess) return attr;
-  hipLaunchKernelGGL((lm_head_ksplit_kernel<NW, NB>), dim3(kLmBlocks), dim3(NW * 64), lds, st, a, row0);
+  hipLaunchKernelGGL((lm_head_ksplit_kernel<NW, NB>), dim3(kLmBlocks), dim3(NW * 64), lds, st, a, row0, halves);
   return hipGetLastError();
 }
 
-// One pass over W per 32 hidden rows (16 for the last odd block).
+// One pass over W per 32 hidden rows (16 for the last odd block); 33 to 64 rows: one pass by
+// paired workgroups.
 template <int NW>
 hipError_t launch_ksplit(const AcceptArgs &a, hipStream_t st) {
+  if (a.M > 32 && a.M <= 64) return launch_ksplit_nb<NW, 2>(a, 0, 2, st);
   for (int row0 = 0; row0 < a.M;) {
     const bool two = a.M - row0 > 16;
-    const hipError_t e = two ? launch_ksplit_nb<NW, 2>(a, row0, st) : launch_ksplit_nb<NW, 1>(a, row0, st);
+    const hipError_t e = two ? launch_ksplit_nb<NW, 2>(a, row0, 1, st) : launch_ksplit_nb<NW, 1>(a, row0, 1, st);
     if (e != hipSuccess) return e;
     row0 += two ? 32 : 16;
   }
