@@ -168,16 +168,20 @@ lm_head_ksplit_kernel(AcceptArgs a, int row0_arg, int halves) {
   auto tile_row0 = [&](int t) { return (wg + t * n_wg) * 16; };
   // 16 loads of 1 KB: load r = the k-slice of row r of the tile (rows clamped to the last row).
   // Issued unconditionally (tile index clamped) so that the number of loads in flight is static.
-  u32x4 buf[16];
-  auto issue = [&](int t) {
+  // one tile (16 KB per wavefront, 112 KB per compute unit) in flight: the weight stream already
+  // saturates HBM with that, a second tile in flight measured 2 us slower
+  constexpr int kBufs = 1;
+  u32x4 buf[kBufs][16];
+  auto issue = [&](int t, u32x4 *bp) {
     const int v0 = tile_row0(min(t, max(n_tiles - 1, 0)));
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
       const int v = min(v0 + r, V - 1);
-      buf[r] = __builtin_nontemporal_load((const u32x4 *)(Wm + (int64_t)v * H + 512 * w + 8 * lane));
+      bp[r] = __builtin_nontemporal_load((const u32x4 *)(Wm + (int64_t)v * H + 512 * w + 8 * lane));
     }
   };
-  issue(0);
+  issue(0, buf[0]);
+  if (kBufs == 2) issue(1, buf[1]);
 
   // B operands: lane (n, c4) holds hidden[row0 + 16 nb + n][512 w + 32 ks + 8 c4 .. +8], ks = 0..15
   bf16x8 hreg[NB][16];
@@ -201,11 +205,11 @@ lm_head_ksplit_kernel(AcceptArgs a, int row0_arg, int halves) {
   int best_i[NB];
 #pragma unroll
   for (int nb = 0; nb < NB; ++nb) { best[nb] = -INFINITY; best_i[nb] = 0x7fffffff; }
-  for (int t = 0; t < n_tiles; ++t) {
+  auto tile_step = [&](int t, u32x4 *bp) {
 #pragma unroll
     for (int r = 0; r < 16; ++r)
-      *reinterpret_cast<u32x4 *>(stg + r * 1024 + (((lane & ~15) | ((lane & 15) ^ r)) << 4)) = buf[r];
-    issue(t + 1);
+      *reinterpret_cast<u32x4 *>(stg + r * 1024 + (((lane & ~15) | ((lane & 15) ^ r)) << 4)) = bp[r];
+    issue(t + kBufs, bp);
     f32x4 acc[NB][2];
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) {
@@ -252,6 +256,11 @@ lm_head_ksplit_kernel(AcceptArgs a, int row0_arg, int halves) {
       }
       __syncthreads();   // reads done before the next partials are written
     }
+  };
+  // (unrolled by the number of register buffers so that each step names its own)
+  for (int t = 0; t < n_tiles; t += kBufs) {
+    tile_step(t, buf[0]);
+    if (kBufs == 2 && t + 1 < n_tiles) tile_step(t + 1, buf[kBufs - 1]);
   }
 
   // a pair's workgroup leaves neutral candidates for the rows of the other half in its slots
