@@ -71,7 +71,10 @@ def test_c1_fp32_accept(sp, oracle):
     ("f32", 256, 1000, 2, 3, False), ("f32", 64, 37, 1, 0, False),
     ("bf16", 512, 4096, 1, 5, False), ("bf16", 3584, 12345, 1, 8, False),
     ("bf16", 3584, 8192, 8, 6, False), ("bf16", 1024, 20000, 1, 60, True),
-    ("bf16", 520, 777, 3, 4, True), ("bf16", 3584, 16, 1, 2, False)])
+    ("bf16", 520, 777, 3, 4, True), ("bf16", 3584, 16, 1, 2, False),
+    # 32, 33 and 64 rows: the last single-pass size, and both ends of the paired-workgroup range
+    ("bf16", 1024, 9000, 4, 7, False), ("bf16", 1024, 9000, 3, 10, False),
+    ("bf16", 3584, 8192, 8, 7, False)])
 def test_accept_shapes(sp, oracle, dtype, H, V, B, n_q, tree):
     cfg = wl.Config("A", dtype, 4, 1, 64, B, None, 8, n_q, tree, H, V)
     parent = None

@@ -101,6 +101,8 @@ def test_verify_context_lengths(sp, oracle, dtype, Hq, Hkv, d, L):
     ((5200, 4100), 8, 0),                  # 33 + 26 splits: more than a quarter padding -> flat grid
     ((5200, 3900), 0, 19),                 # flat grid with two row blocks
     ((6000, 300, 40, 2500, 10), 5, 0),     # very ragged: flat grid, sequences of a single split
+    ((900,), 64, 0),                       # the longest chain the boundary takes (448 rows per KV head)
+    (tuple(20 + 37 * i % 300 for i in range(64)), 2, 0),     # the largest batch the boundary takes
 ])
 def test_verify_batches_cover_both_grid_shapes(sp, oracle, lengths, n_q, nodes):
     """Batches of the matrix-core path (bf16, 28/4 heads, d = 128) in the launch shapes the host
