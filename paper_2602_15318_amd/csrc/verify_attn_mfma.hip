@@ -462,9 +462,9 @@ verify_partial_mfma_kernel(VerifyArgs a, SeqTable tab, PieceTable pt, int rbs, i
 // 18.7 us, 16 x 4 18.5 us.
 constexpr int kCombInFlight = 4;
 
-// kCombWaves = 16 for the decode-time case (one sequence cut into ~64 splits); 4 when no sequence
-// of the call has more than 16 splits (batches), where 16 wavefronts per output tile would mostly
-// find nothing to merge.
+// kCombWaves = 16 for the decode-time case (one sequence cut into ~64 splits); 8 or 4 when no
+// sequence of the call has more than 32 or 16 splits (draft trees, batches), where 16 wavefronts
+// per output tile would mostly find nothing to merge.
 template <int kCombWaves>
 __global__ void __launch_bounds__(64 * kCombWaves)
 verify_combine_tiled_kernel(VerifyArgs a, SeqTable tab, int rbs, int g) {
@@ -590,8 +590,10 @@ hipError_t launch_verify_combine_mfma(const VerifyArgs &a, const SeqTable &tab, 
   dim3 grid(a.Hkv * rbs * 4, 8, a.B);
   int max_ns = 0;
   for (int b = 0; b < a.B; ++b) max_ns = std::max(max_ns, tab.cu_split[b + 1] - tab.cu_split[b]);
-  if (max_ns > 16)
+  if (max_ns > 32)
     hipLaunchKernelGGL(verify_combine_tiled_kernel<16>, grid, dim3(64 * 16), 0, st, a, tab, rbs, a.Hq / a.Hkv);
+  else if (max_ns > 16)
+    hipLaunchKernelGGL(verify_combine_tiled_kernel<8>, grid, dim3(64 * 8), 0, st, a, tab, rbs, a.Hq / a.Hkv);
   else
     hipLaunchKernelGGL(verify_combine_tiled_kernel<4>, grid, dim3(64 * 4), 0, st, a, tab, rbs, a.Hq / a.Hkv);
   return hipGetLastError();

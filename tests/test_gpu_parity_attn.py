@@ -59,6 +59,15 @@ def test_c3_bf16_26k_tree60(sp, oracle, peaked):
     _draft_and_check(sp, oracle, wl.draft_case(wl.C3, 0, peaked=peaked), "C3 draft")
 
 
+@pytest.mark.parametrize("nodes,branching", [(30, (4, 3, 2, 2)), (48, (5, 3, 2, 2, 1)), (16, (4, 2, 1, 1))])
+def test_paper_sized_trees_at_26k_context(sp, oracle, nodes, branching):
+    """Trees of the sizes the paper's total-depth-width settings give (30 and 48 nodes; 16 as a
+    small one) at the full 26,112-token context: 2, 3 and 1 row blocks, 32, 20 and 64 splits."""
+    parent = wl.pruned_tree(0, nodes, branching)
+    c = wl.verify_case(wl.C3, 0, layer=1, n_q=len(parent), parent=parent)
+    _verify_and_check(sp, oracle, c, f"tree of {len(parent)} nodes at 26k")
+
+
 @pytest.mark.parametrize("peaked", [False, True])
 def test_c4_bf16_ragged_batch8(sp, oracle, peaked):
     _verify_and_check(sp, oracle, wl.verify_case(wl.C4, 0, peaked=peaked), "C4 verify")
