@@ -64,9 +64,10 @@ __device__ __forceinline__ float quad_sum(float v) {
   return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
 
-// kQT = 16-row tiles per wavefront: 1 serves up to 64 rows per workgroup (chains), 2 serves 128
-// (draft trees): the K and V^T operands read from LDS then feed two row tiles each, and a tree of
-// R rows needs half as many passes over the K/V stream.
+// kQT = 16-row tiles per wavefront: 1 serves up to 64 rows per workgroup (chains), 2 and 3 serve
+// 128 and 192 (draft trees): the K and V^T operands read from LDS then feed every row tile, and a
+// tree of R rows needs a half or a third as many passes over the K/V stream.  Three tiles take
+// all 256 registers with one step in flight.
 // kPrefetch = steps in flight in registers.  The whole split of a workgroup is only a handful of
 // steps at decode-time sizes (7 at 26k context on 256 compute units), so a deep look-ahead turns
 // the kernel into "load most of it, then compute": depth 1 is fastest there, depth 2 once the
@@ -337,7 +338,7 @@ verify_partial_mfma_kernel(VerifyArgs a, SeqTable tab, PieceTable pt, int rbs, i
           pb[qt][u][e] = (__bf16)p;
         }
         // row sums on the matrix cores: every row of ones . P^T is the sum over the 32 tokens
-        // (with two row tiles the registers do not allow it: per-lane sums, merged at the end)
+        // (kMfmaRowSum off: per-lane sums on the vector ALU, merged across the four lanes at the end)
         if (kMfmaRowSum)
           l_acc[qt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, pb[qt][u], l_acc[qt], 0, 0, 0);
         else
@@ -361,7 +362,7 @@ verify_partial_mfma_kernel(VerifyArgs a, SeqTable tab, PieceTable pt, int rbs, i
     }
   };
 
-  // A wavefront with a partly filled pair of row tiles computes both (the empty one on a zero
+  // A wavefront with a partly filled set of row tiles computes all of them (the empty ones on a zero
   // query): a second, one-tile instance of the step in the same kernel costs more registers than
   // the kernel has.
   auto run = [&](int st, int buf) {
@@ -552,8 +553,13 @@ bool verify_partial_mfma_supported(int dtype, int head_dim) {
 int64_t verify_mfma_unit_floats_o() { return 4 * 4 * 64 * 4; }   // 16 KB: 64 rows x 128 halves
 int64_t verify_mfma_unit_floats_ml() { return kRowsPerWG * kMlFloats; }
 
-// Row blocks per (split, KV head): workgroups of 64 rows for R <= 64, of 128 rows beyond.
-int verify_mfma_row_blocks(int R) { return R <= kRowsPerWG ? 1 : (R + 2 * kRowsPerWG - 1) / (2 * kRowsPerWG); }
+// Row blocks (workgroups per split and KV head) for R rows: blocks of three 64-row tiles unless
+// blocks of two leave fewer empty tiles (7 tiles: 2+2+2+1 beats 3+3+1, measured).
+int verify_mfma_row_blocks(int R) {
+  const int tiles = (R + kRowsPerWG - 1) / kRowsPerWG;
+  const int rbs3 = (tiles + 2) / 3, rbs2 = (tiles + 1) / 2;
+  return rbs3 * 3 - tiles <= rbs2 * 2 - tiles ? rbs3 : rbs2;
+}
 
 hipError_t launch_verify_partial_mfma(const VerifyArgs &a, const SeqTable &tab, hipStream_t st) {
   const int R = a.n_q * (a.Hq / a.Hkv);
@@ -573,9 +579,13 @@ hipError_t launch_verify_partial_mfma(const VerifyArgs &a, const SeqTable &tab, 
   constexpr int kLdsBytes = kStreams * 2 * 2 * kSub * kTileBytes;
   static_assert(kLdsBytes <= 64 * 1024, "beyond 64 KB the kernel needs the dynamic-LDS attribute");
   const int steps = (a.chunk / kTile + kStreams * kSub - 1) / (kStreams * kSub);   // of a full split
-  if (R > kRowsPerWG && steps <= 10)
+  const int tiles = (R + kRowsPerWG - 1) / kRowsPerWG;
+  const int qt = (tiles + rbs - 1) / rbs;
+  if (qt == 3)      // a second tile in flight does not fit the registers (and the step is compute-bound)
+    hipLaunchKernelGGL((verify_partial_mfma_kernel<1, 3>), grid, block, kLdsBytes, st, a, tab, pt, rbs, flat);
+  else if (qt == 2 && steps <= 10)
     hipLaunchKernelGGL((verify_partial_mfma_kernel<1, 2>), grid, block, kLdsBytes, st, a, tab, pt, rbs, flat);
-  else if (R > kRowsPerWG)
+  else if (qt == 2)
     hipLaunchKernelGGL((verify_partial_mfma_kernel<2, 2>), grid, block, kLdsBytes, st, a, tab, pt, rbs, flat);
   else if (steps <= 10)
     hipLaunchKernelGGL((verify_partial_mfma_kernel<1, 1>), grid, block, kLdsBytes, st, a, tab, pt, rbs, flat);

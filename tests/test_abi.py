@@ -124,6 +124,9 @@ def test_workspace_queries(lib):
     # planned in whole groups per XCD: 32 splits x 4 heads x 4 units of 64 rows
     t = lib.sparrow_verify_attn_workspace(ctypes.byref(d), 1, 30, ctypes.c_int64(26142))
     assert 32 * 4 * 4 * 16.5 * 1024 <= t < 12 * 2 ** 20
+    # a 25-node tree (175 rows): one workgroup of 192 rows per (split, KV head), 64 splits
+    t25 = lib.sparrow_verify_attn_workspace(ctypes.byref(d), 1, 25, ctypes.c_int64(26137))
+    assert 64 * 4 * 3 * 16.5 * 1024 <= t25 < 14 * 2 ** 20
     # K/V beyond 2 GB per call: the plain-ALU path with its own layout (fp32 [split, n_q, Hq, d])
     big = lib.sparrow_verify_attn_workspace(ctypes.byref(d), 8, 8, ctypes.c_int64(3_000_000))
     assert big > 0 and big % 256 == 0

@@ -59,10 +59,12 @@ def test_c3_bf16_26k_tree60(sp, oracle, peaked):
     _draft_and_check(sp, oracle, wl.draft_case(wl.C3, 0, peaked=peaked), "C3 draft")
 
 
-@pytest.mark.parametrize("nodes,branching", [(30, (4, 3, 2, 2)), (48, (5, 3, 2, 2, 1)), (16, (4, 2, 1, 1))])
+@pytest.mark.parametrize("nodes,branching", [(30, (4, 3, 2, 2)), (48, (5, 3, 2, 2, 1)), (25, (5, 3, 2, 2, 1)),
+                                             (44, (5, 3, 2, 2, 1)), (16, (4, 2, 1, 1))])
 def test_paper_sized_trees_at_26k_context(sp, oracle, nodes, branching):
-    """Trees of the sizes the paper's total-depth-width settings give (30 and 48 nodes; 16 as a
-    small one) at the full 26,112-token context: 2, 3 and 1 row blocks, 32, 20 and 64 splits."""
+    """Trees of the sizes the paper's total-depth-width settings give (30, 48 and 25 nodes; 44 and
+    16 for the other row-block shapes) at the full 26,112-token context: 4, 6, 3, 5 and 2 tiles of
+    64 rows per KV head, run as workgroups of 2+2, 3+3, 3, 3+2 and 2 tiles."""
     parent = wl.pruned_tree(0, nodes, branching)
     c = wl.verify_case(wl.C3, 0, layer=1, n_q=len(parent), parent=parent)
     _verify_and_check(sp, oracle, c, f"tree of {len(parent)} nodes at 26k")
