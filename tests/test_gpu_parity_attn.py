@@ -126,6 +126,18 @@ def test_verify_batches_cover_both_grid_shapes(sp, oracle, lengths, n_q, nodes):
     _verify_and_check(sp, oracle, c, f"batch {lengths} n_q={c.n_q}")
 
 
+@pytest.mark.parametrize("Hq,Hkv,nodes", [(4, 4, 0), (4, 4, 33), (32, 2, 0), (32, 2, 40), (32, 2, 64), (16, 1, 21)])
+def test_verify_head_groupings(sp, oracle, Hq, Hkv, nodes):
+    """Group sizes other than the 7 of the benchmarked model on the matrix-core path (d = 128):
+    no grouping at all (one query head per KV head) and 16 query heads per KV head, where a tree
+    of 64 nodes is 1,024 rows per KV head (16 tiles of 64 rows, 8 workgroups per split)."""
+    cfg = _cfg("bf16", Hq, Hkv, 128)
+    parent = wl.pruned_tree(11, nodes, (4, 3, 2, 2, 1, 1)) if nodes else None
+    c = wl.verify_case(cfg, seed=Hq + nodes, layouts=(((wl.TEXT, 1300),), ((wl.TEXT, 75),)),
+                       n_q=len(parent) if nodes else 7, parent=parent)
+    _verify_and_check(sp, oracle, c, f"Hq={Hq} Hkv={Hkv} n_q={c.n_q}")
+
+
 @pytest.mark.parametrize("seed", range(10))
 def test_verify_random_batches(sp, oracle, seed):
     """Seeded random batches on the matrix-core path: 1-7 sequences of 1-4000 context tokens
