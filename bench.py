@@ -393,6 +393,10 @@ def main() -> int:
                                 ("tree_16", 16, (4, 2, 1, 1))):
             par_t = wl.pruned_tree(args.seed, nodes, br)
             other[name + "_at_C3_context"] = time_verify(wl.C3, 8, len(par_t), par_t)
+        # the chain with the last accepted token's row verified too (k + 1 = 9 rows, 63 per KV head)
+        other["chain_of_k_plus_1_rows_at_C5_context"] = time_verify(wl.C5, 8, cfg.n_q + 1, None)
+        other["tree_25_5_8_at_C3_context"] = time_verify(
+            wl.C3, 8, 25, wl.pruned_tree(args.seed, 25, (5, 3, 2, 2, 1)))
         result["other_configs"] = other
 
     # ---------------------------------------------------------------- CPU oracle beside it
