@@ -28,8 +28,11 @@
  *    first call of an entry point in a process may do one-time set-up of its
  *    kernels (raising their LDS limit), so make one call outside capture first.
  *  - Errors: every entry point returns a sparrow_status (0 = ok, negative =
- *    error); on error nothing has been enqueued and sparrow_last_error()
- *    describes the reason.  Contents of device arrays (text_idx ascending and
+ *    error) and sparrow_last_error() describes the reason.  On a validation
+ *    error (INVALID_ARG, UNSUPPORTED, WORKSPACE) nothing has been enqueued;
+ *    SPARROW_ERR_DEVICE means the HIP runtime refused a launch, and earlier
+ *    kernels of the same call may already be enqueued (the outputs are then
+ *    unspecified).  Contents of device arrays (text_idx ascending and
  *    in range, parent[i] in [-1, i)) are preconditions that cannot be checked
  *    without a device read; violating them gives undefined results but never
  *    an out-of-bounds access as long as indices stay inside the sequence.
@@ -126,8 +129,8 @@ int sparrow_draft_window_attn(const sparrow_attn_desc *desc, const void *q, cons
  *  out        dev [B*n_q, Hq, d]
  *  lse        dev float [B*n_q, Hq] or NULL
  *  workspace  dev, at least sparrow_verify_attn_workspace() bytes, 256-byte aligned; holds the
- *             split-context partial results (running max, sum, unnormalised output)
- *  total_tokens = cu_seqlens[B]
+ *             per-split partial results in a format internal to the library
+ *  total_tokens = cu_seqlens[B] - cu_seqlens[0], the rows of the call's sequences
  *  B = 0 or n_q = 0: SPARROW_OK and nothing is enqueued.
  */
 size_t sparrow_verify_attn_workspace(const sparrow_attn_desc *desc, int32_t B, int32_t n_q,

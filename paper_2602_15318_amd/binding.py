@@ -193,7 +193,7 @@ def verify_attn(q, k, v, cu_seqlens, parent, n_q: int, scale: float = 0.0, out=N
     out = torch.empty_like(q) if out is None else out
     if lse is None and want_lse:
         lse = torch.empty(q.shape[:2], dtype=torch.float32, device=q.device)
-    need = int(lib.sparrow_verify_attn_workspace(ctypes.byref(d), B, n_q, int(cu[-1]))) if B > 0 else 0
+    need = int(lib.sparrow_verify_attn_workspace(ctypes.byref(d), B, n_q, int(cu[-1]) - int(cu[0]))) if B > 0 else 0
     ws = _workspace(need, q.device, workspace)
     args = (ctypes.byref(d), _ptr(q), _ptr(k), _ptr(v), _i32p(cu), _ptr(parent), B, int(n_q),
             _ptr(out), _ptr(lse), _ptr(ws), 0 if ws is None else ws.numel() * ws.element_size(),

@@ -333,7 +333,7 @@ int sparrow_verify_attn_passes(const sparrow_attn_desc *desc, const void *q, con
     if (cu_seqlens[b + 1] - cu_seqlens[b] < n_q)
       return fail(SPARROW_ERR_INVALID_ARG, "sequence %d has %d rows, fewer than its n_q = %d draft rows",
                   b, cu_seqlens[b + 1] - cu_seqlens[b], n_q);
-  const int64_t total = cu_seqlens[B];   // the figure the workspace query is given
+  const int64_t total = (int64_t)cu_seqlens[B] - cu_seqlens[0];   // the figure the workspace query is given
   const bool mfma = use_mfma_verify(desc, total);
   // Splits per sequence in proportion to its length (at least one), within the budget of about one
   // workgroup per compute unit that plan_chunk aims at; each sequence is then cut into equal

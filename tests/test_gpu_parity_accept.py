@@ -74,12 +74,17 @@ def test_c1_fp32_accept(sp, oracle):
     ("bf16", 520, 777, 3, 4, True), ("bf16", 3584, 16, 1, 2, False),
     # 32, 33 and 64 rows: the last single-pass size, and both ends of the paired-workgroup range
     ("bf16", 1024, 9000, 4, 7, False), ("bf16", 1024, 9000, 3, 10, False),
-    ("bf16", 3584, 8192, 8, 7, False)])
+    ("bf16", 3584, 8192, 8, 7, False),
+    # hidden 4096: the eight-wavefront k-split instances at 9, 32, 33 and 64 rows (one block of 16
+    # rows, one pass of 32, and both ends of the paired-workgroup range)
+    ("bf16", 4096, 6000, 1, 8, False), ("bf16", 4096, 6000, 4, 7, False),
+    ("bf16", 4096, 6000, 3, 10, False), ("bf16", 4096, 6000, 8, 7, False),
+    ("bf16", 4096, 5000, 1, 48, True)])
 def test_accept_shapes(sp, oracle, dtype, H, V, B, n_q, tree):
     cfg = wl.Config("A", dtype, 4, 1, 64, B, None, 8, n_q, tree, H, V)
     parent = None
     if tree:
-        parent = wl.pruned_tree(7, n_q, (4, 3, 2, 2, 1, 1) if n_q == 60 else (2, 2))
+        parent = wl.pruned_tree(7, n_q, (4, 3, 2, 2, 1, 1) if n_q >= 48 else (2, 2))
         n_q = len(parent)
     # first seed of V, V+1000, ... whose oracle margins are all wide enough (decided on the CPU)
     for seed in range(V, V + 5000, 1000):

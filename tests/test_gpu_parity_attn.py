@@ -18,7 +18,10 @@ def sp():
 
 from gpu_util import check_attn, dev, host, run_draft, run_verify  # noqa: E402
 
-LSE_TOL = {"f32": 2e-5, "bf16": 2e-2}
+# lse is an fp32 output.  Matrix-core path: the row sums add probabilities rounded to bf16 (2^-9
+# relative each, so at most ln(1 + 2^-9) = 2e-3 on lse if every rounding went the same way) on top
+# of fp32 rounding of the scores (~1e-4 at |score| ~ 30).
+LSE_TOL = {"f32": 2e-5, "bf16": 4e-3}
 
 
 def _verify_and_check(sp, oracle, c, what):
@@ -256,6 +259,42 @@ def test_head_major_kv_layout(sp, oracle, interleaved):
         torch.cuda.synchronize()
         ref, _ = oracle.draft_window_attn(dc.q, dc.k, dc.v, dc.cu_seqlens, dc.text_idx, dc.cu_text, dc.window)
         check_attn(host(out), ref, dtype, f"head-major draft {dtype}")
+
+
+def test_kv_span_of_2_gib_takes_the_plain_alu_kernels(sp, oracle):
+    """bf16, d = 128, but the K/V rows lie 8 MiB apart in one 2.2 GB allocation: a sequence's rows
+    can then no longer be addressed by the 32-bit offsets of the matrix-core kernel, and the call
+    (and its workspace query) fall back to the plain-ALU partial and combine kernels in bf16 with
+    head_dim 128 and 64-bit addressing.  Chain and a small tree, two sequences."""
+    import torch
+    cfg = _cfg("bf16", 28, 4, 128)
+    stride = 1 << 22                              # elements between consecutive tokens
+    lay = (((wl.TEXT, 20), (wl.VISUAL, 200), (wl.TEXT, 37)), ((wl.TEXT, 3),))
+    for parent in (None, wl.pruned_tree(3, 9, (3, 2, 1))):
+        n_q = 6 if parent is None else len(parent)
+        c = wl.verify_case(cfg, seed=31 + n_q, layouts=lay, n_q=n_q, parent=parent)
+        T = c.k.shape[0]
+        assert T * stride * 2 >= 2 ** 31, "the case must span 2 GiB to leave the matrix-core path"
+        buf = torch.empty(T * stride, dtype=torch.bfloat16, device="cuda").view(T, stride)
+        k = buf[:, :512].view(T, 4, 128)
+        v = buf[:, stride // 2:stride // 2 + 512].view(T, 4, 128)
+        k.copy_(dev(c.k, "bf16"))
+        v.copy_(dev(c.v, "bf16"))
+        q = dev(c.q, "bf16")
+        par = None if parent is None else dev(parent)
+        out, lse = sp.verify_attn(q, k, v, c.cu_seqlens, par, n_q)
+        torch.cuda.synchronize()
+        ref, ref_lse = oracle.verify_attn(c.q, c.k, c.v, c.cu_seqlens, parent, n_q)
+        check_attn(host(out), ref, "bf16", f"2 GiB span, n_q={n_q}")
+        assert np.abs(host(lse) - ref_lse).max() <= LSE_TOL["bf16"]
+        # the same rows packed densely run on the matrix cores: a different workspace layout
+        # (fp16 tiles per 64-row block against fp32 rows per split), so the two queries differ
+        dense_k = dev(c.k, "bf16")
+        need_far = sp.verify_attn_workspace_bytes(q, k, v, 2, n_q, T)
+        need_dense = sp.verify_attn_workspace_bytes(q, dense_k, dense_k, 2, n_q, T)
+        assert need_far != need_dense and need_far > 0
+        del buf, k, v
+        torch.cuda.empty_cache()
 
 
 def test_large_v_does_not_overflow_the_split_partials(sp, oracle):

@@ -48,8 +48,6 @@ SHAPES = [
 @pytest.mark.parametrize("dtype,Hq,Hkv,d,H", SHAPES)
 @pytest.mark.parametrize("M", [1, 9, 16, 17, 64])
 def test_hsr_fc(sp, oracle, dtype, Hq, Hkv, d, H, M):
-    if H >= 3584 and M in (9, 17):
-        pytest.skip("the large widths run M = 1, 16, 64")
     cfg = _cfg(dtype, Hq, Hkv, d, H)
     c = wl.hsr_case(cfg, seed=M, rows=M, vocab=2048)
     z = sp.hsr_fc(dev(c.embed, dtype), dev(c.token_ids), dev(c.h_prev, dtype), dev(c.w_fc, dtype),
@@ -66,8 +64,6 @@ def test_hsr_fc(sp, oracle, dtype, Hq, Hkv, d, H, M):
 @pytest.mark.parametrize("dtype,Hq,Hkv,d,H", SHAPES)
 @pytest.mark.parametrize("M", [1, 8, 16, 33, 64])
 def test_draft_qkv_append(sp, oracle, dtype, Hq, Hkv, d, H, M):
-    if H >= 3584 and M in (8, 33):
-        pytest.skip("the large widths run M = 1, 16, 64")
     cfg = _cfg(dtype, Hq, Hkv, d, H)
     rng = np.random.default_rng(1000 + M)
     T = 300

@@ -31,7 +31,9 @@ from gpu_util import dev  # noqa: E402
     ("f32", 256, 70, 1, 16),          # chunks of 2 tokens, some rounds exhaust a chunk
     ("bf16", 512, 5000, 10, 10),
     ("bf16", 3584, 8192, 8, 8),       # k-split lm_head
-    ("bf16", 3584, 4096, 40, 6),      # three passes of the k-split kernel
+    ("bf16", 3584, 4096, 40, 6),      # 40 rows: the paired-workgroup pass of the k-split kernel
+    ("bf16", 4096, 4096, 9, 8),       # k-split lm_head, eight wavefronts
+    ("bf16", 4096, 3000, 33, 5),      # ... and its paired-workgroup pass
 ])
 def test_draft_topk(sp, oracle, dtype, H, V, M, k):
     cfg = wl.Config("tk", dtype, 4, 1, 64, 1, (((wl.TEXT, 8),),), 8, 4, False, H, V)
