@@ -153,6 +153,30 @@ int sparrow_verify_attn_passes(const sparrow_attn_desc *desc, const void *q, con
                                size_t workspace_bytes, void *hip_stream, int32_t passes);
 
 /*
+ * sparrow_verify_attn for callers that cannot allocate device memory or hand over a workspace:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, validation, kernels and results as sparrow_verify_attn, minus the workspace: the
+ * split partials go to a scratch array of SPARROW_STATIC_WS_BYTES that is part of the library's
+ * device code (one copy per GPU, held until the process ends).  The call allocates and frees
+ * nothing.  The device that owns hip_stream and the buffers must be the current device.
+ *  - A call whose partials need more than SPARROW_STATIC_WS_BYTES returns
+ *    SPARROW_ERR_UNSUPPORTED and enqueues nothing (the message states the size; use
+ *    sparrow_verify_attn with a caller workspace).  Every configuration of the benchmark fits:
+ *    one 26k-token layer with a chain of 8 takes 4.3 MB, with a 60-node tree 7.7 MB, the ragged
+ *    batch of 8 takes 4.9 MB.
+ *  - All calls on one GPU share that GPU's array: calls that may overlap in time (different
+ *    streams, different host threads with different streams) race on it; calls on one stream
+ *    are ordered and safe.  Nothing in the array has to start at zero (the combine pass only
+ *    reads what the partial pass of the same call wrote), so no clearing is enqueued.
+ *  - The first call on a GPU looks the array's device address up (and may load the library's
+ *    code object onto that GPU): make it outside graph capture.
+ */
+#define SPARROW_STATIC_WS_BYTES (16u * 1024u * 1024u)
+int sparrow_verify_attn_static(const sparrow_attn_desc *desc, const void *q, const void *k,
+                               const void *v, const int32_t *cu_seqlens, const int32_t *parent,
+                               int32_t B, int32_t n_q, void *out, float *lse, void *hip_stream);
+
+/*
  * Greedy (temperature 0, lossless) acceptance: logits = hidden_rows . lm_head^T,
  * target token of every row = lowest index attaining the row maximum, then the
  * longest accepted path: starting at the last accepted token (row 0), move to

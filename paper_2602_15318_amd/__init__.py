@@ -7,7 +7,8 @@ PyTorch only provides device memory and streams.
 __all__ = ["SparrowError", "accept", "accept_workspace_bytes", "draft_window_attn", "last_error",
            "library_path", "verify_attn", "verify_attn_workspace_bytes", "version", "AttnDesc",
            "lib", "hsr_fc", "draft_qkv_append", "kv_commit", "accept_sample",
-           "accept_sample_workspace_bytes", "draft_topk", "TreePool", "stream_read"]
+           "accept_sample_workspace_bytes", "draft_topk", "TreePool", "stream_read",
+           "verify_attn_static", "STATIC_WS_BYTES"]
 
 
 def __getattr__(name):

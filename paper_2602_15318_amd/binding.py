@@ -53,6 +53,9 @@ def _load() -> ctypes.CDLL:
     L.sparrow_verify_attn.restype = ctypes.c_int
     L.sparrow_verify_attn.argtypes = [dp, vp, vp, vp, i32p, vp, ctypes.c_int32, ctypes.c_int32,
                                       vp, fp, vp, ctypes.c_size_t, vp]
+    L.sparrow_verify_attn_static.restype = ctypes.c_int
+    L.sparrow_verify_attn_static.argtypes = [dp, vp, vp, vp, i32p, vp, ctypes.c_int32, ctypes.c_int32,
+                                             vp, fp, vp]
     L.sparrow_verify_attn_passes.restype = ctypes.c_int
     L.sparrow_verify_attn_passes.argtypes = L.sparrow_verify_attn.argtypes + [ctypes.c_int32]
     L.sparrow_accept_workspace.restype = ctypes.c_size_t
@@ -202,6 +205,24 @@ def verify_attn(q, k, v, cu_seqlens, parent, n_q: int, scale: float = 0.0, out=N
         _check(lib.sparrow_verify_attn(*args))
     else:
         _check(lib.sparrow_verify_attn_passes(*args, int(passes)))
+    return out, lse
+
+
+STATIC_WS_BYTES = 16 * 1024 * 1024      # SPARROW_STATIC_WS_BYTES
+
+
+def verify_attn_static(q, k, v, cu_seqlens, parent, n_q: int, out, lse=None, scale: float = 0.0,
+                       stream=None):
+    """sparrow_verify_attn_static: the verification attention on the library's own scratch.  The
+    caller passes every output; nothing is allocated here or in the library."""
+    cu = _host_i32(cu_seqlens)
+    B = cu.shape[0] - 1
+    d = _desc(q, k, v, scale)
+    if parent is not None and (parent.dtype != torch.int32 or parent.numel() != n_q):
+        raise ValueError("parent must be an int32 tensor with n_q entries")
+    _check(lib.sparrow_verify_attn_static(ctypes.byref(d), _ptr(q), _ptr(k), _ptr(v), _i32p(cu),
+                                          _ptr(parent), B, int(n_q), _ptr(out), _ptr(lse),
+                                          _stream_ptr(stream)))
     return out, lse
 
 

@@ -2,6 +2,7 @@
 // kernel selection and launches.  No device allocation, no synchronisation, no device reads.
 #include <hip/hip_runtime.h>
 
+#include <atomic>
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
@@ -14,6 +15,12 @@
 #include "hsr_input.hpp"
 #include "kv_commit.hpp"
 #include "verify_attn.hpp"
+
+// Library-owned scratch of sparrow_verify_attn_static: one copy per GPU, held from the moment the
+// code object is loaded on that GPU until the process ends.  In host code the name `scratch` is
+// only a handle for hipGetSymbolAddress; the device address that call yields differs per GPU and
+// is what the kernels are given.
+static __device__ __align__(256) unsigned char scratch[SPARROW_STATIC_WS_BYTES];
 
 namespace sparrow {
 int generic_num_candidates(int V);
@@ -115,6 +122,26 @@ size_t verify_ws_bytes(const sparrow_attn_desc *d, int64_t max_slots, int32_t n_
   size_t bo, bml;
   verify_ws_layout(d, max_slots, n_q, mfma, &bo, &bml);
   return bo + bml;
+}
+
+constexpr int kMaxDevices = 64;
+std::atomic<void *> g_scratch_ptr[kMaxDevices];
+
+// Device address of `scratch` on the current device (looked up once per device).
+int static_scratch(void **out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return fail(SPARROW_ERR_DEVICE, "hipGetDevice: %s", hipGetErrorString(e));
+  if (dev < 0 || dev >= kMaxDevices) return fail(SPARROW_ERR_UNSUPPORTED, "device index %d (0..%d)", dev, kMaxDevices - 1);
+  void *p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+  if (p == nullptr) {
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || p == nullptr)
+      return fail(SPARROW_ERR_DEVICE, "hipGetSymbolAddress(scratch) on device %d: %s", dev, hipGetErrorString(e));
+    g_scratch_ptr[dev].store(p, std::memory_order_release);   // every thread finds the same address
+  }
+  *out = p;
+  return SPARROW_OK;
 }
 }  // namespace
 }  // namespace sparrow
@@ -313,10 +340,12 @@ int sparrow_verify_attn(const sparrow_attn_desc *desc, const void *q, const void
                                     workspace_bytes, hip_stream, 3);
 }
 
-int sparrow_verify_attn_passes(const sparrow_attn_desc *desc, const void *q, const void *k,
-                               const void *v, const int32_t *cu_seqlens, const int32_t *parent,
-                               int32_t B, int32_t n_q, void *out, float *lse, void *workspace,
-                               size_t workspace_bytes, void *hip_stream, int32_t passes) {
+// Shared body.  static_ws: the workspace is the library's own scratch array (looked up here, after
+// validation, so that an invalid call never touches the device).
+static int verify_body(const sparrow_attn_desc *desc, const void *q, const void *k,
+                       const void *v, const int32_t *cu_seqlens, const int32_t *parent,
+                       int32_t B, int32_t n_q, void *out, float *lse, void *workspace,
+                       size_t workspace_bytes, void *hip_stream, int32_t passes, bool static_ws) {
   g_err[0] = 0;
   if (passes < 1 || passes > 3) return fail(SPARROW_ERR_INVALID_ARG, "passes = %d (1, 2 or 3)", passes);
   if (int rc = check_desc(desc)) return rc;
@@ -373,6 +402,15 @@ int sparrow_verify_attn_passes(const sparrow_attn_desc *desc, const void *q, con
   }
   const int n_slots = tab.cu_split[B];
   const size_t need = verify_ws_bytes(desc, n_slots, n_q, mfma);
+  if (static_ws) {
+    if (need > (size_t)SPARROW_STATIC_WS_BYTES)
+      return fail(SPARROW_ERR_UNSUPPORTED,
+                  "this call needs %zu bytes of split partials, the static scratch holds %zu: use "
+                  "sparrow_verify_attn with a workspace of the caller's",
+                  need, (size_t)SPARROW_STATIC_WS_BYTES);
+    if (int rc = static_scratch(&workspace)) return rc;
+    workspace_bytes = SPARROW_STATIC_WS_BYTES;
+  }
   if (!workspace || workspace_bytes < need)
     return fail(SPARROW_ERR_WORKSPACE, "workspace of %zu bytes needed, %zu given%s", need,
                 workspace_bytes, workspace ? "" : " (NULL)");
@@ -400,6 +438,21 @@ int sparrow_verify_attn_passes(const sparrow_attn_desc *desc, const void *q, con
     if (e != hipSuccess) return fail(SPARROW_ERR_DEVICE, "verify combine launch: %s", hipGetErrorString(e));
   }
   return SPARROW_OK;
+}
+
+int sparrow_verify_attn_passes(const sparrow_attn_desc *desc, const void *q, const void *k,
+                               const void *v, const int32_t *cu_seqlens, const int32_t *parent,
+                               int32_t B, int32_t n_q, void *out, float *lse, void *workspace,
+                               size_t workspace_bytes, void *hip_stream, int32_t passes) {
+  return verify_body(desc, q, k, v, cu_seqlens, parent, B, n_q, out, lse, workspace, workspace_bytes,
+                     hip_stream, passes, false);
+}
+
+int sparrow_verify_attn_static(const sparrow_attn_desc *desc, const void *q, const void *k,
+                               const void *v, const int32_t *cu_seqlens, const int32_t *parent,
+                               int32_t B, int32_t n_q, void *out, float *lse, void *hip_stream) {
+  return verify_body(desc, q, k, v, cu_seqlens, parent, B, n_q, out, lse, nullptr, 0, hip_stream, 3,
+                     true);
 }
 
 // ------------------------------------------------------------------ acceptance
