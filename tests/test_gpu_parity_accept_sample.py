@@ -75,7 +75,7 @@ CASES = [
     ("bf16", 3584, 2048, 2, 20, True, 1.0, 0.6),       # 42 rows: two passes of the k-split kernel
     ("bf16", 1024, 3000, 1, 8, False, 2.0, 0.5),       # fallback matrix-core lm_head
     ("bf16", 4096, 4096, 1, 8, False, 1.0, 0.6),       # k-split lm_head, eight wavefronts
-    ("bf16", 4096, 2048, 3, 12, True, 1.0, 0.6),       # 39 rows: its paired-workgroup pass
+    ("bf16", 4096, 2048, 2, 20, True, 1.0, 0.6),       # 42 rows: its paired-workgroup pass
 ]
 
 
