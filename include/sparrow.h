@@ -367,9 +367,14 @@ int sparrow_kv_commit(const sparrow_attn_desc *desc, void *const *k_layers, void
  * once, with the same 16-byte non-temporal loads the attention kernels use, and does nothing
  * else; bench.py times it on a layer's K and V to show what moving those bytes costs on the
  * device at hand.  dev_ptr 16-byte aligned, bytes a multiple of 16; sink dev, 4 bytes, may be
- * written.
+ * written.  sparrow_stream_read_shape chooses the launch: `workgroups` of 256 lanes (1..65536),
+ * `loads_in_flight` per lane (2, 4, 8 or 16), and `regions` = 0 (the grid sweeps the range front
+ * to back) or 1 (every workgroup reads one contiguous region of its own); sparrow_stream_read is
+ * the shape (1024, 8, 0).
  */
 int sparrow_stream_read(const void *dev_ptr, size_t bytes, void *sink, void *hip_stream);
+int sparrow_stream_read_shape(const void *dev_ptr, size_t bytes, void *sink, int32_t workgroups,
+                              int32_t loads_in_flight, int32_t regions, void *hip_stream);
 
 /* Thread-local description of the last error on this thread; "" if none. */
 const char *sparrow_last_error(void);

@@ -92,6 +92,9 @@ def _load() -> ctypes.CDLL:
     L.sparrow_tree_select.argtypes = [vp, vp, vp, ctypes.c_int32, ctypes.c_int32, vp, vp, vp, vp]
     L.sparrow_stream_read.restype = ctypes.c_int
     L.sparrow_stream_read.argtypes = [vp, ctypes.c_size_t, vp, vp]
+    L.sparrow_stream_read_shape.restype = ctypes.c_int
+    L.sparrow_stream_read_shape.argtypes = [vp, ctypes.c_size_t, vp, ctypes.c_int32, ctypes.c_int32,
+                                            ctypes.c_int32, vp]
     return L
 
 
@@ -437,8 +440,15 @@ class TreePool:
         return parent, ids, pidx
 
 
-def stream_read(t: torch.Tensor, sink: torch.Tensor, stream=None) -> None:
-    """sparrow_stream_read over the storage of a contiguous tensor (measurement aid)."""
+def stream_read(t: torch.Tensor, sink: torch.Tensor, stream=None, shape=None) -> None:
+    """sparrow_stream_read over the storage of a contiguous tensor (measurement aid); `shape` =
+    (workgroups, loads_in_flight, regions) selects sparrow_stream_read_shape."""
     if not t.is_contiguous():
         raise ValueError("stream_read needs a contiguous tensor")
-    _check(lib.sparrow_stream_read(_ptr(t), t.numel() * t.element_size(), _ptr(sink), _stream_ptr(stream)))
+    nbytes = t.numel() * t.element_size()
+    if shape is None:
+        _check(lib.sparrow_stream_read(_ptr(t), nbytes, _ptr(sink), _stream_ptr(stream)))
+    else:
+        wgs, in_flight, regions = shape
+        _check(lib.sparrow_stream_read_shape(_ptr(t), nbytes, _ptr(sink), int(wgs), int(in_flight),
+                                             int(regions), _stream_ptr(stream)))

@@ -24,7 +24,8 @@ static __device__ __align__(256) unsigned char scratch[SPARROW_STATIC_WS_BYTES];
 
 namespace sparrow {
 int generic_num_candidates(int V);
-hipError_t launch_stream_read(const void *p, size_t bytes, unsigned int *sink, hipStream_t st);
+hipError_t launch_stream_read(const void *p, size_t bytes, unsigned int *sink, int workgroups,
+                              int in_flight, int regions, hipStream_t st);
 
 namespace {
 thread_local char g_err[512] = "";
@@ -264,14 +265,24 @@ int sparrow_kv_commit(const sparrow_attn_desc *desc, void *const *k_layers, void
   return SPARROW_OK;
 }
 
-int sparrow_stream_read(const void *dev_ptr, size_t bytes, void *sink, void *hip_stream) {
+int sparrow_stream_read_shape(const void *dev_ptr, size_t bytes, void *sink, int32_t workgroups,
+                              int32_t loads_in_flight, int32_t regions, void *hip_stream) {
   g_err[0] = 0;
   if (bytes == 0) return SPARROW_OK;
   if (!dev_ptr || !sink || !aligned16(dev_ptr) || bytes % 16 != 0)
     return fail(SPARROW_ERR_INVALID_ARG, "stream_read: NULL or misaligned pointer, or bytes not a multiple of 16");
-  const hipError_t e = launch_stream_read(dev_ptr, bytes, (unsigned int *)sink, (hipStream_t)hip_stream);
+  if (workgroups < 1 || workgroups > 65536)
+    return fail(SPARROW_ERR_INVALID_ARG, "stream_read: workgroups = %d (1..65536)", workgroups);
+  if (loads_in_flight != 2 && loads_in_flight != 4 && loads_in_flight != 8 && loads_in_flight != 16)
+    return fail(SPARROW_ERR_UNSUPPORTED, "stream_read: loads_in_flight = %d (2, 4, 8 or 16)", loads_in_flight);
+  const hipError_t e = launch_stream_read(dev_ptr, bytes, (unsigned int *)sink, workgroups, loads_in_flight,
+                                          regions != 0, (hipStream_t)hip_stream);
   if (e != hipSuccess) return fail(SPARROW_ERR_DEVICE, "stream_read launch: %s", hipGetErrorString(e));
   return SPARROW_OK;
+}
+
+int sparrow_stream_read(const void *dev_ptr, size_t bytes, void *sink, void *hip_stream) {
+  return sparrow_stream_read_shape(dev_ptr, bytes, sink, 1024, 8, 0, hip_stream);
 }
 
 const char *sparrow_last_error(void) { return g_err; }
