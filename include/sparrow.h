@@ -64,6 +64,7 @@ typedef enum { SPARROW_F32 = 0, SPARROW_BF16 = 1 } sparrow_dtype;
 /* Limits (SPARROW_ERR_UNSUPPORTED beyond them). */
 #define SPARROW_MAX_BATCH 64   /* sequences per call */
 #define SPARROW_MAX_NQ 64      /* draft rows (chain length or tree nodes) per sequence */
+#define SPARROW_MAX_ACCEPT_ROWS 512   /* logit rows B*(n_q+1) of one acceptance call */
 
 /* Shared by both attention calls. */
 typedef struct {
@@ -80,6 +81,10 @@ typedef struct {
                               stride_head spans all T tokens is the caller's precondition).
                               Head-major lets a workgroup stream one contiguous range per KV
                               head and measures ~4 % faster on the verification attention. */
+  int32_t parent_stride;   /* sparrow_verify_attn only: 0 = `parent` holds one tree [n_q] shared by
+                              all sequences of the call; >= n_q = every sequence has a tree of its
+                              own (dynamic draft trees differ between requests), sequence b's
+                              parents at parent[b*parent_stride + i].  Ignored if parent is NULL. */
 } sparrow_attn_desc;
 
 /*
@@ -125,7 +130,8 @@ int sparrow_draft_window_attn(const sparrow_attn_desc *desc, const void *q, cons
  *  cu_seqlens host int32 [B+1]  sequence b owns rows cu_seqlens[b] .. cu_seqlens[b+1]-1
  *                               (= L_b + n_q rows, L_b >= 0)
  *  parent     dev int32 [n_q]   tree shared by all sequences: parent[i] in [-1, i), -1 = child of
- *                               the last accepted token; NULL = chain (parent[i] = i-1)
+ *                               the last accepted token; NULL = chain (parent[i] = i-1).  With
+ *                               desc->parent_stride >= n_q: one tree per sequence, [B, parent_stride]
  *  out        dev [B*n_q, Hq, d]
  *  lse        dev float [B*n_q, Hq] or NULL
  *  workspace  dev, at least sparrow_verify_attn_workspace() bytes, 256-byte aligned; holds the
@@ -194,7 +200,11 @@ int sparrow_verify_attn_static(const sparrow_attn_desc *desc, const void *q, con
  *  accept_path dev int32 out [B*n_q]    accepted node indices root-first, -1 padded
  *  bonus_id    dev int32 out [B]        target token at the last accepted row
  *  workspace   dev, at least sparrow_accept_workspace() bytes (per-tile argmax candidates)
- *  Limits: B*(n_q+1) <= 64 rows.  n_q = 0 is allowed (plain greedy decode of row 0).
+ *  Limits: B*(n_q+1) <= SPARROW_MAX_ACCEPT_ROWS logit rows (the weights are streamed once per 64
+ *  rows).  n_q = 0 is allowed (plain greedy decode of row 0).
+ * sparrow_accept_trees: the same with one draft tree per sequence (a batch of requests that each
+ *  grew a dynamic tree): parent dev int32 [B, parent_stride], parent_stride >= n_q (0 = the shared
+ *  [n_q] form of sparrow_accept).
  */
 size_t sparrow_accept_workspace(int32_t dtype, int32_t B, int32_t n_q, int32_t hidden,
                                 int32_t vocab);
@@ -203,6 +213,11 @@ int sparrow_accept(int32_t dtype, const void *hidden_rows, const void *lm_head,
                    int32_t hidden, int32_t vocab, int32_t *target_ids, int32_t *accept_len,
                    int32_t *accept_path, int32_t *bonus_id, void *workspace,
                    size_t workspace_bytes, void *hip_stream);
+int sparrow_accept_trees(int32_t dtype, const void *hidden_rows, const void *lm_head,
+                         const int32_t *draft_ids, const int32_t *parent, int32_t parent_stride,
+                         int32_t B, int32_t n_q, int32_t hidden, int32_t vocab, int32_t *target_ids,
+                         int32_t *accept_len, int32_t *accept_path, int32_t *bonus_id,
+                         void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
  * Stochastic acceptance at temperature > 0, lossless (the paper's "Temp = 1"
@@ -239,6 +254,15 @@ int sparrow_accept_sample(int32_t dtype, const void *hidden_rows, const void *lm
                           const float *u_bonus, int32_t *accept_len, int32_t *accept_path,
                           int32_t *bonus_id, void *workspace, size_t workspace_bytes,
                           void *hip_stream);
+/* The same with one draft tree per sequence: parent dev int32 [B, parent_stride] (see
+ * sparrow_accept_trees). */
+int sparrow_accept_sample_trees(int32_t dtype, const void *hidden_rows, const void *lm_head,
+                                const int32_t *draft_ids, const int32_t *parent,
+                                int32_t parent_stride, int32_t B, int32_t n_q, int32_t hidden,
+                                int32_t vocab, float temperature, const float *u_accept,
+                                const float *u_bonus, int32_t *accept_len, int32_t *accept_path,
+                                int32_t *bonus_id, void *workspace, size_t workspace_bytes,
+                                void *hip_stream);
 
 /*
  * Dynamic draft tree (Experiment section: dynamic tree structure with the
@@ -258,7 +282,7 @@ int sparrow_accept_sample(int32_t dtype, const void *hidden_rows, const void *lm
  *   logits in decreasing order with their natural-log softmax values.
  *   hidden_rows dev [M, hidden], lm_head dev [vocab, hidden]; ids dev int32 out [M, k];
  *   logp dev float out [M, k]; workspace dev >= sparrow_draft_topk_workspace() bytes, 256-byte
- *   aligned.  Limits: M <= 64, 1 <= k <= 16, k <= vocab <= 262,144.
+ *   aligned.  Limits: M <= SPARROW_MAX_ACCEPT_ROWS, 1 <= k <= 16, k <= vocab <= 262,144.
  * sparrow_tree_expand: one level.  front_in dev int32 [n_front] pool indices of the frontier (NULL
  *   at level 0: the root, n_front = 1); cand_ids dev int32 / cand_logp dev float [n_front, width]
  *   (rows of sparrow_draft_topk for the frontier nodes); the candidates are appended to the pool

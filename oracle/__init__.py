@@ -101,11 +101,23 @@ def verify_attn(q, k, v, cu_seqlens, parent, n_q: int,
                 scale: Optional[float] = None) -> Tuple[np.ndarray, np.ndarray]:
     """q [B*n_q,Hq,d]; k,v [sum(L_b+n_q),Hkv,d]; parent int32 [n_q] or None (chain).
     Returns (out [B*n_q,Hq,d], lse [B*n_q,Hq])."""
+    cu = _i32(cu_seqlens)
+    B = cu.shape[0] - 1
+    if parent is not None and np.ndim(parent) == 2:
+        # one tree per sequence [B, n_q]: by definition the per-sequence results, each sequence
+        # verified on its own with its own tree
+        par2 = _i32(parent)
+        assert par2.shape == (B, n_q)
+        outs, lses = [], []
+        for b in range(B):
+            o, l = verify_attn(np.asarray(q)[b * n_q:(b + 1) * n_q], np.asarray(k)[cu[b]:cu[b + 1]],
+                               np.asarray(v)[cu[b]:cu[b + 1]], [0, cu[b + 1] - cu[b]], par2[b], n_q, scale)
+            outs.append(o)
+            lses.append(l)
+        return np.concatenate(outs), np.concatenate(lses)
     q, k, v = _f64(q), _f64(k), _f64(v)
     rows, Hq, d = q.shape
     T, Hkv, _ = k.shape
-    cu = _i32(cu_seqlens)
-    B = cu.shape[0] - 1
     assert rows == B * n_q and v.shape == k.shape
     par = None if parent is None else _i32(parent)
     out = np.empty((rows, Hq, d), dtype=np.float64)
@@ -154,6 +166,12 @@ def accept(target_ids, draft_ids, parent, B: int, n_q: int):
     """Returns (accept_len [B], accept_path [B,n_q], bonus_id [B])."""
     t, dr = _i32(target_ids), _i32(draft_ids)
     assert t.shape == (B * (n_q + 1),) and dr.shape == (B * n_q,)
+    if parent is not None and np.ndim(parent) == 2:      # one tree per sequence: per-sequence walks
+        par2 = _i32(parent)
+        assert par2.shape == (B, n_q)
+        parts = [accept(t[b * (n_q + 1):(b + 1) * (n_q + 1)], dr[b * n_q:(b + 1) * n_q], par2[b], 1, n_q)
+                 for b in range(B)]
+        return tuple(np.concatenate([p[i] for p in parts]) for i in range(3))
     par = None if parent is None else _i32(parent)
     alen = np.empty(B, dtype=np.int32)
     path = np.empty((B, max(n_q, 0)), dtype=np.int32)
@@ -263,6 +281,13 @@ def accept_sample(lg, draft_ids, parent, B: int, n_q: int, temperature: float, u
     V = lg.shape[1]
     assert lg.shape[0] == B * (n_q + 1)
     dr = _i32(draft_ids)
+    if parent is not None and np.ndim(parent) == 2:      # one tree per sequence: per-sequence walks
+        par2 = _i32(parent)
+        assert par2.shape == (B, n_q)
+        ua2, ub2 = np.asarray(u_accept).reshape(B, n_q), np.asarray(u_bonus).reshape(B)
+        parts = [accept_sample(lg[b * (n_q + 1):(b + 1) * (n_q + 1)], dr[b * n_q:(b + 1) * n_q], par2[b],
+                               1, n_q, temperature, ua2[b:b + 1], ub2[b:b + 1]) for b in range(B)]
+        return tuple(np.concatenate([p[i] for p in parts]) for i in range(4))
     par = None if parent is None else _i32(parent)
     ua, ub = _f64(u_accept).reshape(B, max(n_q, 0)), _f64(u_bonus)
     alen = np.empty(B, dtype=np.int32)

@@ -30,7 +30,7 @@ class AttnDesc(ctypes.Structure):
     _fields_ = [("dtype", ctypes.c_int32), ("n_q_heads", ctypes.c_int32),
                 ("n_kv_heads", ctypes.c_int32), ("head_dim", ctypes.c_int32),
                 ("scale", ctypes.c_float), ("kv_stride_token", ctypes.c_int64),
-                ("kv_stride_head", ctypes.c_int64)]
+                ("kv_stride_head", ctypes.c_int64), ("parent_stride", ctypes.c_int32)]
 
 
 def _load() -> ctypes.CDLL:
@@ -64,6 +64,15 @@ def _load() -> ctypes.CDLL:
     L.sparrow_accept.argtypes = [ctypes.c_int32, vp, vp, vp, vp, ctypes.c_int32, ctypes.c_int32,
                                  ctypes.c_int32, ctypes.c_int32, vp, vp, vp, vp, vp,
                                  ctypes.c_size_t, vp]
+    L.sparrow_accept_trees.restype = ctypes.c_int
+    L.sparrow_accept_trees.argtypes = [ctypes.c_int32, vp, vp, vp, vp, ctypes.c_int32, ctypes.c_int32,
+                                       ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, vp, vp, vp, vp,
+                                       vp, ctypes.c_size_t, vp]
+    L.sparrow_accept_sample_trees.restype = ctypes.c_int
+    L.sparrow_accept_sample_trees.argtypes = [ctypes.c_int32, vp, vp, vp, vp, ctypes.c_int32,
+                                              ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
+                                              ctypes.c_int32, ctypes.c_float, vp, vp, vp, vp, vp, vp,
+                                              ctypes.c_size_t, vp]
     L.sparrow_hsr_fc.restype = ctypes.c_int
     L.sparrow_hsr_fc.argtypes = [ctypes.c_int32, vp, vp, vp, vp, vp, ctypes.c_int32, ctypes.c_int32,
                                  ctypes.c_int32, vp, vp]
@@ -143,13 +152,27 @@ def _stream_ptr(stream) -> ctypes.c_void_p:
     return ctypes.c_void_p(s.cuda_stream)
 
 
-def _desc(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, scale: float) -> AttnDesc:
+def _parent_stride(parent: Optional[torch.Tensor], n_q: int, B: int) -> int:
+    """0 for a tree [n_q] shared by all sequences, the row stride for per-sequence trees [B, n_q]."""
+    if parent is None:
+        return 0
+    if parent.dtype != torch.int32:
+        raise ValueError("parent must be an int32 tensor")
+    if parent.dim() == 1 and parent.numel() == n_q and parent.is_contiguous():
+        return 0
+    if parent.dim() == 2 and tuple(parent.shape) == (B, n_q) and parent.stride(1) == 1 and n_q > 0:
+        return int(parent.stride(0)) if B > 1 else n_q
+    raise ValueError("parent must be int32 [n_q] (one tree for all sequences) or [B, n_q]")
+
+
+def _desc(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, scale: float,
+          parent_stride: int = 0) -> AttnDesc:
     if k.dim() != 3 or k.stride(2) != 1 or v.stride() != k.stride() or v.shape != k.shape:
         raise ValueError("k and v must be [T, Hkv, d] with identical strides and a contiguous d")
     if not q.is_contiguous():
         raise ValueError("q must be contiguous [rows, Hq, d]")
     return AttnDesc(_dtype_code(q), q.shape[1], k.shape[1], q.shape[2], float(scale),
-                    k.stride(0), k.stride(1))
+                    k.stride(0), k.stride(1), int(parent_stride))
 
 
 def _workspace(nbytes: int, device, workspace: Optional[torch.Tensor]) -> Optional[torch.Tensor]:
@@ -189,13 +212,11 @@ def verify_attn_workspace_bytes(q, k, v, B: int, n_q: int, total_tokens: int,
 def verify_attn(q, k, v, cu_seqlens, parent, n_q: int, scale: float = 0.0, out=None, lse=None,
                 want_lse: bool = True, workspace=None, stream=None, passes: int = 3):
     """sparrow_verify_attn (sparrow_verify_attn_passes when passes != 3).  q [B*n_q,Hq,d];
-    k,v [sum(L_b+n_q),Hkv,d]; parent int32 device tensor [n_q] or None (chain).
-    Returns (out, lse)."""
+    k,v [sum(L_b+n_q),Hkv,d]; parent int32 device tensor [n_q] (one tree for all sequences),
+    [B, n_q] (one tree per sequence) or None (chain).  Returns (out, lse)."""
     cu = _host_i32(cu_seqlens)
     B = cu.shape[0] - 1
-    d = _desc(q, k, v, scale)
-    if parent is not None and (parent.dtype != torch.int32 or parent.numel() != n_q):
-        raise ValueError("parent must be an int32 tensor with n_q entries")
+    d = _desc(q, k, v, scale, _parent_stride(parent, n_q, B))
     out = torch.empty_like(q) if out is None else out
     if lse is None and want_lse:
         lse = torch.empty(q.shape[:2], dtype=torch.float32, device=q.device)
@@ -220,9 +241,7 @@ def verify_attn_static(q, k, v, cu_seqlens, parent, n_q: int, out, lse=None, sca
     caller passes every output; nothing is allocated here or in the library."""
     cu = _host_i32(cu_seqlens)
     B = cu.shape[0] - 1
-    d = _desc(q, k, v, scale)
-    if parent is not None and (parent.dtype != torch.int32 or parent.numel() != n_q):
-        raise ValueError("parent must be an int32 tensor with n_q entries")
+    d = _desc(q, k, v, scale, _parent_stride(parent, n_q, B))
     _check(lib.sparrow_verify_attn_static(ctypes.byref(d), _ptr(q), _ptr(k), _ptr(v), _i32p(cu),
                                           _ptr(parent), B, int(n_q), _ptr(out), _ptr(lse),
                                           _stream_ptr(stream)))
@@ -255,8 +274,9 @@ def accept(hidden_rows, lm_head, draft_ids, parent, B: int, n_q: int, workspace=
     path = outputs["accept_path"]
     if n_q > 0 and not path.is_contiguous():
         raise ValueError("accept_path must be contiguous")
-    _check(lib.sparrow_accept(code, _ptr(hidden_rows), _ptr(lm_head), _ptr(draft_ids),
-                              _ptr(parent), B, n_q, H, V, _ptr(outputs["target_ids"]),
+    _check(lib.sparrow_accept_trees(code, _ptr(hidden_rows), _ptr(lm_head), _ptr(draft_ids),
+                              _ptr(parent), _parent_stride(parent, n_q, B), B, n_q, H, V,
+                              _ptr(outputs["target_ids"]),
                               _ptr(outputs["accept_len"]), _ptr(path) if n_q > 0 else None,
                               _ptr(outputs["bonus_id"]), _ptr(ws),
                               0 if ws is None else ws.numel() * ws.element_size(),
@@ -372,8 +392,9 @@ def accept_sample(hidden_rows, lm_head, draft_ids, parent, B: int, n_q: int, tem
         outputs = {"accept_len": torch.empty(B, dtype=torch.int32, device=dev),
                    "accept_path": torch.empty((B, n_q), dtype=torch.int32, device=dev),
                    "bonus_id": torch.empty(B, dtype=torch.int32, device=dev)}
-    _check(lib.sparrow_accept_sample(code, _ptr(hidden_rows), _ptr(lm_head), _ptr(draft_ids),
-                                     _ptr(parent), B, n_q, H, V, float(temperature),
+    _check(lib.sparrow_accept_sample_trees(code, _ptr(hidden_rows), _ptr(lm_head), _ptr(draft_ids),
+                                     _ptr(parent), _parent_stride(parent, n_q, B), B, n_q, H, V,
+                                     float(temperature),
                                      _ptr(u_accept), _ptr(u_bonus), _ptr(outputs["accept_len"]),
                                      _ptr(outputs["accept_path"]) if n_q > 0 else None,
                                      _ptr(outputs["bonus_id"]), _ptr(ws),

@@ -93,9 +93,9 @@ __global__ void __launch_bounds__(1024) accept_finalize_kernel(AcceptArgs a) {
   // draft tokens and parents of every sequence into LDS while the candidates are being reduced:
   // the walk below is a chain of dependent reads and should not pay a memory round trip each
   if (tid < a.B * a.n_q) {
-    const int j = tid % a.n_q;
+    const int j = tid % a.n_q, b = tid / a.n_q;
     dr_s[tid] = a.draft_ids[tid];
-    par_s[tid] = a.parent ? a.parent[j] : j - 1;
+    par_s[tid] = a.parent ? a.parent[(int64_t)b * a.parent_stride + j] : j - 1;
   }
   // two rows per wavefront at a time (rows r and r + 16): their candidate loads are in flight
   // together, and the 64-lane argmax runs on the vector ALU (maximum, then the lowest index

@@ -7,13 +7,14 @@
 
 namespace sparrow {
 
-constexpr int kAcceptMaxRows = 64;
+constexpr int kAcceptMaxRows = SPARROW_MAX_ACCEPT_ROWS;
 
 struct AcceptArgs {
   const void *hidden;        // [M, H]
   const void *lm_head;       // [V, H]
   const int32_t *draft_ids;  // [B*n_q]
-  const int32_t *parent;     // [n_q] or nullptr
+  const int32_t *parent;     // [n_q] (parent_stride 0) or [B, parent_stride], or nullptr
+  int32_t parent_stride;
   int32_t B, n_q, M, H, V;   // M = B*(n_q+1)
   int32_t n_cand;            // argmax candidates per row produced by the GEMM pass
   float *cand_val;           // [M, n_cand]
@@ -28,7 +29,8 @@ constexpr int kSampleMaxVocab = 1 << 20;   // the bonus draw keeps one fp64 sum 
 struct SampleArgs {
   const float *logits;       // [M, V]
   const int32_t *draft_ids;  // [B*n_q]
-  const int32_t *parent;     // [n_q] or nullptr
+  const int32_t *parent;     // [n_q] (parent_stride 0) or [B, parent_stride], or nullptr
+  int32_t parent_stride;
   const float *u_accept;     // [B, n_q]
   const float *u_bonus;      // [B]
   float *stats;              // [M, kStatChunks, 2]: max and sum of exponentials per chunk

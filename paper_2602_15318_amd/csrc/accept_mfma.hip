@@ -308,16 +308,17 @@ hipError_t launch_ksplit_nb(const AcceptArgs &a, int row0, int halves, hipStream
   return hipGetLastError();
 }
 
-// One pass over W per 32 hidden rows (16 for the last odd block); 33 to 64 rows: one pass by
-// paired workgroups.
+// One pass over W per 64 hidden rows by paired workgroups while more than 32 rows are left, then
+// one pass for the last 17 to 32 rows, or for the last 16 or fewer.
 template <int NW>
 hipError_t launch_ksplit(const AcceptArgs &a, hipStream_t st) {
-  if (a.M > 32 && a.M <= 64) return launch_ksplit_nb<NW, 2>(a, 0, 2, st);
   for (int row0 = 0; row0 < a.M;) {
-    const bool two = a.M - row0 > 16;
-    const hipError_t e = two ? launch_ksplit_nb<NW, 2>(a, row0, 1, st) : launch_ksplit_nb<NW, 1>(a, row0, 1, st);
+    const int left = a.M - row0;
+    hipError_t e;
+    if (left > 32) { e = launch_ksplit_nb<NW, 2>(a, row0, 2, st); row0 += 64; }
+    else if (left > 16) { e = launch_ksplit_nb<NW, 2>(a, row0, 1, st); row0 += 32; }
+    else { e = launch_ksplit_nb<NW, 1>(a, row0, 1, st); row0 += 16; }
     if (e != hipSuccess) return e;
-    row0 += two ? 32 : 16;
   }
   return hipSuccess;
 }

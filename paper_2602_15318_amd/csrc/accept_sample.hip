@@ -130,7 +130,7 @@ accept_sample_kernel(SampleArgs a) {
     const float m = sh_m, Z = sh_Z;
     // ---- children of cur and the probabilities of their tokens
     if (tid < n_q) {
-      const int pj = a.parent ? a.parent[tid] : tid - 1;
+      const int pj = a.parent ? a.parent[(int64_t)b * a.parent_stride + tid] : tid - 1;
       const int x = dr[tid];
       float p = -1.f;
       if (pj == cur && x >= 0 && x < V) p = fast_exp2(lg[x] * a.inv_temp_log2 - m) / Z;

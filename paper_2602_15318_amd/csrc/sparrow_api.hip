@@ -373,6 +373,9 @@ static int verify_body(const sparrow_attn_desc *desc, const void *q, const void 
     if (cu_seqlens[b + 1] - cu_seqlens[b] < n_q)
       return fail(SPARROW_ERR_INVALID_ARG, "sequence %d has %d rows, fewer than its n_q = %d draft rows",
                   b, cu_seqlens[b + 1] - cu_seqlens[b], n_q);
+  if (parent && desc->parent_stride != 0 && desc->parent_stride < n_q)
+    return fail(SPARROW_ERR_INVALID_ARG, "parent_stride = %d must be 0 (one shared tree) or at least n_q = %d",
+                desc->parent_stride, n_q);
   const int64_t total = (int64_t)cu_seqlens[B] - cu_seqlens[0];   // the figure the workspace query is given
   const bool mfma = use_mfma_verify(desc, total);
   // Splits per sequence in proportion to its length (at least one), within the budget of about one
@@ -429,6 +432,7 @@ static int verify_body(const sparrow_attn_desc *desc, const void *q, const void 
     return fail(SPARROW_ERR_INVALID_ARG, "workspace must be 256-byte aligned");
   VerifyArgs a;
   a.q = q; a.k = k; a.v = v; a.parent = parent;
+  a.parent_stride = parent ? desc->parent_stride : 0;
   a.B = B; a.n_q = n_q; a.Hq = desc->n_q_heads; a.Hkv = desc->n_kv_heads; a.d = desc->head_dim;
   a.chunk = chunk; a.n_slots = n_slots;
   a.scale_log2 = scale_log2_of(desc);
@@ -501,7 +505,8 @@ size_t sparrow_accept_sample_workspace(int32_t dtype, int32_t B, int32_t n_q, in
 }
 
 static int accept_body(int32_t dtype, const void *hidden_rows, const void *lm_head,
-                       const int32_t *draft_ids, const int32_t *parent, int32_t B, int32_t n_q,
+                       const int32_t *draft_ids, const int32_t *parent, int32_t parent_stride,
+                       int32_t B, int32_t n_q,
                        int32_t hidden, int32_t vocab, int32_t *target_ids, int32_t *accept_len,
                        int32_t *accept_path, int32_t *bonus_id, void *workspace,
                        size_t workspace_bytes, void *hip_stream, const SampleParams *sample) {
@@ -514,6 +519,9 @@ static int accept_body(int32_t dtype, const void *hidden_rows, const void *lm_he
   if ((int64_t)B * (n_q + 1) > kAcceptMaxRows)
     return fail(SPARROW_ERR_UNSUPPORTED, "B*(n_q+1) = %lld rows exceeds %d", (long long)B * (n_q + 1), kAcceptMaxRows);
   if (hidden <= 0 || vocab <= 0) return fail(SPARROW_ERR_INVALID_ARG, "hidden = %d, vocab = %d", hidden, vocab);
+  if (parent && parent_stride != 0 && parent_stride < n_q)
+    return fail(SPARROW_ERR_INVALID_ARG, "parent_stride = %d must be 0 (one shared tree) or at least n_q = %d",
+                parent_stride, n_q);
   const int per = dtype == SPARROW_BF16 ? 8 : 4;
   if (hidden % per != 0)
     return fail(SPARROW_ERR_UNSUPPORTED, "hidden = %d must be a multiple of %d (16-byte rows)", hidden, per);
@@ -543,6 +551,7 @@ static int accept_body(int32_t dtype, const void *hidden_rows, const void *lm_he
     return fail(SPARROW_ERR_INVALID_ARG, "workspace must be 256-byte aligned");
   AcceptArgs a;
   a.hidden = hidden_rows; a.lm_head = lm_head; a.draft_ids = draft_ids; a.parent = parent;
+  a.parent_stride = parent ? parent_stride : 0;
   a.B = B; a.n_q = n_q; a.M = M; a.H = hidden; a.V = vocab; a.n_cand = n_cand;
   a.cand_val = (float *)workspace;
   a.cand_idx = (int32_t *)((char *)workspace + round_up((size_t)M * n_cand * sizeof(float), 256));
@@ -559,6 +568,7 @@ static int accept_body(int32_t dtype, const void *hidden_rows, const void *lm_he
   }
   SampleArgs s;
   s.logits = a.logits; s.draft_ids = draft_ids; s.parent = parent;
+  s.parent_stride = a.parent_stride;
   s.u_accept = sample->u_accept; s.u_bonus = sample->u_bonus;
   s.stats = (float *)((char *)workspace + base + logits_bytes);
   s.blk_sum = (float *)((char *)workspace + base + logits_bytes + stats_bytes);
@@ -572,14 +582,37 @@ static int accept_body(int32_t dtype, const void *hidden_rows, const void *lm_he
   return SPARROW_OK;
 }
 
+int sparrow_accept_trees(int32_t dtype, const void *hidden_rows, const void *lm_head,
+                         const int32_t *draft_ids, const int32_t *parent, int32_t parent_stride,
+                         int32_t B, int32_t n_q, int32_t hidden, int32_t vocab, int32_t *target_ids,
+                         int32_t *accept_len, int32_t *accept_path, int32_t *bonus_id,
+                         void *workspace, size_t workspace_bytes, void *hip_stream) {
+  return accept_body(dtype, hidden_rows, lm_head, draft_ids, parent, parent_stride, B, n_q, hidden,
+                     vocab, target_ids, accept_len, accept_path, bonus_id, workspace, workspace_bytes,
+                     hip_stream, nullptr);
+}
+
 int sparrow_accept(int32_t dtype, const void *hidden_rows, const void *lm_head,
                    const int32_t *draft_ids, const int32_t *parent, int32_t B, int32_t n_q,
                    int32_t hidden, int32_t vocab, int32_t *target_ids, int32_t *accept_len,
                    int32_t *accept_path, int32_t *bonus_id, void *workspace,
                    size_t workspace_bytes, void *hip_stream) {
-  return accept_body(dtype, hidden_rows, lm_head, draft_ids, parent, B, n_q, hidden, vocab,
-                     target_ids, accept_len, accept_path, bonus_id, workspace, workspace_bytes,
-                     hip_stream, nullptr);
+  return sparrow_accept_trees(dtype, hidden_rows, lm_head, draft_ids, parent, 0, B, n_q, hidden, vocab,
+                              target_ids, accept_len, accept_path, bonus_id, workspace,
+                              workspace_bytes, hip_stream);
+}
+
+int sparrow_accept_sample_trees(int32_t dtype, const void *hidden_rows, const void *lm_head,
+                                const int32_t *draft_ids, const int32_t *parent,
+                                int32_t parent_stride, int32_t B, int32_t n_q, int32_t hidden,
+                                int32_t vocab, float temperature, const float *u_accept,
+                                const float *u_bonus, int32_t *accept_len, int32_t *accept_path,
+                                int32_t *bonus_id, void *workspace, size_t workspace_bytes,
+                                void *hip_stream) {
+  const SampleParams sp_ = {temperature, u_accept, u_bonus};
+  return accept_body(dtype, hidden_rows, lm_head, draft_ids, parent, parent_stride, B, n_q, hidden,
+                     vocab, nullptr, accept_len, accept_path, bonus_id, workspace, workspace_bytes,
+                     hip_stream, &sp_);
 }
 
 int sparrow_accept_sample(int32_t dtype, const void *hidden_rows, const void *lm_head,
@@ -588,10 +621,9 @@ int sparrow_accept_sample(int32_t dtype, const void *hidden_rows, const void *lm
                           const float *u_bonus, int32_t *accept_len, int32_t *accept_path,
                           int32_t *bonus_id, void *workspace, size_t workspace_bytes,
                           void *hip_stream) {
-  const SampleParams sp_ = {temperature, u_accept, u_bonus};
-  return accept_body(dtype, hidden_rows, lm_head, draft_ids, parent, B, n_q, hidden, vocab,
-                     nullptr, accept_len, accept_path, bonus_id, workspace, workspace_bytes,
-                     hip_stream, &sp_);
+  return sparrow_accept_sample_trees(dtype, hidden_rows, lm_head, draft_ids, parent, 0, B, n_q, hidden,
+                                     vocab, temperature, u_accept, u_bonus, accept_len, accept_path,
+                                     bonus_id, workspace, workspace_bytes, hip_stream);
 }
 
 // ------------------------------------------------------------------ dynamic draft tree

@@ -18,6 +18,7 @@ struct SeqTable {
 struct VerifyArgs {
   const void *q, *k, *v;
   const int32_t *parent;  // device, or nullptr for a chain
+  int32_t parent_stride;  // 0: one tree [n_q] for all sequences; else sequence b's tree at parent + b*stride
   int32_t B, n_q, Hq, Hkv, d;
   int32_t chunk;          // longest split of the call, in tokens (the kernels derive each
                           // sequence's own split length from SeqTable)

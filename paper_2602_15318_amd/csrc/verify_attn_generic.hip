@@ -56,7 +56,7 @@ verify_partial_generic_kernel(VerifyArgs a, SeqTable tab) {
   }
   if (tid < kGenRows) {
     int rho = rb * kGenRows + tid;
-    Anc[tid] = rho < R ? ancestor_mask(a.parent, rho / g) : 0ull;
+    Anc[tid] = rho < R ? ancestor_mask(a.parent ? a.parent + (int64_t)b * a.parent_stride : nullptr, rho / g) : 0ull;
   }
 
   // score phase: thread -> (token tt, row group rg); rows rg and rg + 8

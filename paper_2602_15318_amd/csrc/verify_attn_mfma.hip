@@ -237,7 +237,8 @@ verify_partial_mfma_kernel(VerifyArgs a, SeqTable tab, PieceTable pt, int rbs, i
   for (int qt = 0; qt < kQT; ++qt) {
     anc[qt] = 0ull;
     if (t1 > L) {                                            // uniform over the workgroup
-      anc[qt] = ancestor_mask_wave(a.parent, a.n_q, i_row[qt], lane);
+      anc[qt] = ancestor_mask_wave(a.parent ? a.parent + (int64_t)b * a.parent_stride : nullptr, a.n_q,
+                                   i_row[qt], lane);
       if (!row_ok[qt]) anc[qt] = 0ull;
     }
   }

@@ -33,11 +33,11 @@ class Desc(ctypes.Structure):
     _fields_ = [("dtype", ctypes.c_int32), ("n_q_heads", ctypes.c_int32),
                 ("n_kv_heads", ctypes.c_int32), ("head_dim", ctypes.c_int32),
                 ("scale", ctypes.c_float), ("kv_stride_token", ctypes.c_int64),
-                ("kv_stride_head", ctypes.c_int64)]
+                ("kv_stride_head", ctypes.c_int64), ("parent_stride", ctypes.c_int32)]
 
 
 def desc(dtype=1, hq=28, hkv=4, d=128, scale=0.0, st=None, sh=None):
-    return Desc(dtype, hq, hkv, d, scale, hkv * d if st is None else st, d if sh is None else sh)
+    return Desc(dtype, hq, hkv, d, scale, hkv * d if st is None else st, d if sh is None else sh, 0)
 
 
 def test_every_declared_symbol_is_exported(lib):
@@ -108,7 +108,8 @@ def test_accept_argument_validation(lib):
         i32(dtype), P, P, P, None, i32(B), i32(n_q), i32(H), i32(V), P, P, P, P, ws,
         ctypes.c_size_t(wsb), None)
     assert call(dtype=3) == UNSUPPORTED
-    assert call(B=8, n_q=8) == UNSUPPORTED            # 72 rows > 64
+    assert call(B=8, n_q=64) == UNSUPPORTED           # 520 logit rows > 512
+    assert call(B=8, n_q=8) == WORKSPACE              # 72 rows: valid since the limit is 512
     assert call(H=3580) == UNSUPPORTED                # rows not multiples of 16 bytes
     assert call(V=0) == INVALID
     assert call() == WORKSPACE
@@ -197,7 +198,7 @@ def test_accept_sample_and_tree_argument_validation(lib):
         i32(1), P, P, i32(M), i32(3584), i32(V), i32(k), P, P, ws, ctypes.c_size_t(wsb), None)
     assert topk(k=17) == UNSUPPORTED
     assert topk(k=0) == UNSUPPORTED
-    assert topk(M=65) == UNSUPPORTED
+    assert topk(M=513) == UNSUPPORTED
     assert topk(V=300000) == UNSUPPORTED
     assert topk(V=4, k=8) == UNSUPPORTED                   # more tokens asked for than there are
     assert topk() == WORKSPACE

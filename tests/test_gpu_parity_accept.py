@@ -113,6 +113,54 @@ def _depths(parent, n_q):
     return d
 
 
+@pytest.mark.parametrize("dtype,H,V,B,nodes", [
+    ("bf16", 3584, 8192, 8, 30),      # 8 requests x 30-node trees: 248 logit rows, four 64-row passes
+    ("bf16", 4096, 4096, 3, 25),      # 78 rows: one paired pass and one 16-row pass
+    ("bf16", 1024, 5000, 5, 12),      # 65 rows on the fallback matrix-core kernel
+    ("f32", 256, 1000, 7, 9),         # 70 rows on the plain-ALU kernel
+    ("bf16", 3584, 2048, 8, 63),      # 512 rows, the most one call takes
+])
+def test_accept_one_tree_per_sequence_and_many_rows(sp, oracle, dtype, H, V, B, nodes):
+    """Every sequence of the batch has a draft tree of its own (parent [B, n_q]) and the call holds
+    more than 64 logit rows: target ids, accepted length, path and bonus token of every sequence
+    against the oracle run sequence by sequence, random drafts and planted paths of every depth."""
+    branching = (4, 3, 2, 2, 1, 1) if nodes > 12 else (3, 2, 2)
+    trees = np.stack([wl.pruned_tree(200 + i, nodes, branching) for i in range(B)])
+    n_q = trees.shape[1]
+    cfg = wl.Config("A", dtype, 4, 1, 64, B, None, 8, n_q, True, H, V)
+    # planted rows (each a scaled lm_head row plus noise): with up to 512 rows, random rows would
+    # hardly ever all have a top-1 / top-2 gap above MARGIN
+    c = wl.accept_case(cfg, seed=V, batch=B, n_q=n_q, parent=trees, planted=True)
+    ref = oracle.accept_step(c.hidden, c.lm_head, c.draft_ids, trees, B, n_q)
+    np.testing.assert_array_equal(ref["target_ids"], c.planted_ids)
+    W = dev(c.lm_head, dtype)
+    _check(run_accept(sp, c, B, lm_head_dev=W), ref, "random drafts")
+    rng = np.random.default_rng(V + B)
+    t = ref["target_ids"].reshape(B, n_q + 1)
+    for trial in range(2):
+        ids = rng.integers(0, V, size=(B, n_q)).astype(np.int32)
+        want = []
+        for b in range(B):
+            par = trees[b]
+            for j in range(n_q):
+                while ids[b, j] == t[b, par[j] + 1]:
+                    ids[b, j] = (ids[b, j] + 1) % V
+            cur, depth = -1, int(rng.integers(0, 7))
+            n_acc = 0
+            for _ in range(depth):
+                kids = np.flatnonzero(par == cur)
+                if len(kids) == 0:
+                    break
+                pick = kids[int(rng.integers(0, len(kids)))]
+                ids[b, pick] = t[b, cur + 1]
+                cur = pick
+                n_acc += 1
+            want.append(n_acc)
+        r = oracle.accept_step(c.hidden, c.lm_head, ids.reshape(-1), trees, B, n_q)
+        np.testing.assert_array_equal(r["accept_len"], want)
+        _check(run_accept(sp, c, B, draft_ids=ids.reshape(-1), lm_head_dev=W), r, f"planted {want}")
+
+
 def test_exact_ties_take_lowest_id(sp, oracle):
     """Duplicated lm_head rows give bit-equal logits on both sides: the lower id must win, also
     when the duplicates fall into different tiles / wavefronts of the GEMM pass."""

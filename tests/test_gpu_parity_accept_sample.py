@@ -102,6 +102,41 @@ def test_accept_sample_matches_oracle(sp, oracle, dtype, H, V, B, n_q, tree, T, 
     assert graded >= 2, "fewer than two well-conditioned seeds among 8"
 
 
+def test_accept_sample_one_tree_per_sequence(sp, oracle):
+    """parent [B, n_q]: every sequence walks its own tree (70 logit rows: two passes of lm_head)."""
+    dtype, H, V, B, nodes, T = "bf16", 3584, 2048, 5, 13, 1.0
+    trees = np.stack([wl.pruned_tree(300 + i, nodes, (3, 2, 2, 1, 1, 1)) for i in range(B)])
+    n_q = trees.shape[1]
+    cfg = wl.Config("as", dtype, 4, 1, 64, B, (((wl.TEXT, 8),),) * B, 8, n_q, True, H, V)
+    graded = 0
+    for seed in range(12):
+        # drafts planted along each sequence's own tree
+        ac = wl.accept_case(cfg, seed, vocab=V, batch=B, n_q=n_q, parent=trees, planted=True)
+        rng = np.random.default_rng(seed + 77)
+        draft = ac.draft_ids.reshape(B, n_q).copy()
+        t = ac.planted_ids.reshape(B, n_q + 1)
+        for b in range(B):
+            for j in range(n_q):
+                if rng.random() < 0.6:
+                    draft[b, j] = t[b, trees[b, j] + 1]
+        draft = draft.reshape(-1).astype(np.int32)
+        ua = rng.random((B, n_q)).astype(np.float32)
+        ub = rng.random(B).astype(np.float32)
+        hidden = _damped(ac.hidden, H, V, dtype)
+        ref = oracle.accept_sample_step(hidden, ac.lm_head, draft, trees, B, n_q, T, ua, ub)
+        if ref["margin"].min() < MARGIN:
+            continue
+        r = sp.accept_sample(dev(hidden, dtype), dev(ac.lm_head, dtype), dev(draft), dev(trees), B, n_q, T,
+                             dev(ua), dev(ub))
+        torch.cuda.synchronize()
+        for key in ("accept_len", "accept_path", "bonus_id"):
+            np.testing.assert_array_equal(r[key].cpu().numpy(), ref[key], err_msg=f"seed {seed}: {key}")
+        graded += 1
+        if graded == 2:
+            break
+    assert graded >= 1, "no well-conditioned seed among 12"
+
+
 def test_accept_sample_walk_depths_are_exercised(oracle):
     """The cases above are only worth something if walks of different depths, rejections followed
     by acceptances, and bonus draws after strike-outs all occur: count them on the CPU (the test

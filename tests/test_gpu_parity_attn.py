@@ -185,6 +185,37 @@ def test_verify_trees(sp, oracle, dtype, Hq, Hkv, d):
     np.testing.assert_array_equal(a, b)
 
 
+@pytest.mark.parametrize("dtype,Hq,Hkv,d", [("f32", 4, 1, 64), ("bf16", 28, 4, 128), ("bf16", 8, 2, 64)])
+def test_verify_one_tree_per_sequence(sp, oracle, dtype, Hq, Hkv, d):
+    """A batch in which every sequence grew a draft tree of its own (dynamic trees differ between
+    requests): parent is [B, n_q], and each sequence's rows follow its own ancestor sets.  Checked
+    against the oracle run sequence by sequence with that sequence's tree, on both kernel paths,
+    both grid shapes of the matrix-core path (even and very uneven lengths) and through the
+    entry point on the library's static scratch."""
+    import torch
+    cfg = _cfg(dtype, Hq, Hkv, d)
+    for lengths, nodes in (((1500, 1400, 1450), 30), ((2600, 90, 700, 5), 48), ((300, 200), 7)):
+        branching = (4, 3, 2, 2, 1, 1) if nodes > 8 else (3, 2)
+        trees = np.stack([wl.pruned_tree(100 + i, nodes, branching) for i in range(len(lengths))])
+        n_q = trees.shape[1]
+        assert any(not np.array_equal(trees[0], t) for t in trees[1:]), "the trees must differ"
+        lay = tuple(((wl.TEXT, n),) for n in lengths)
+        c = wl.verify_case(cfg, seed=nodes, layouts=lay, n_q=n_q, parent=trees)
+        _verify_and_check(sp, oracle, c, f"per-sequence trees {dtype} {lengths} n_q={n_q}")
+        # the same call with every sequence on tree 0 must differ (the per-sequence trees are used)
+        c0 = wl.verify_case(cfg, seed=nodes, layouts=lay, n_q=n_q, parent=trees[0])
+        a, _ = run_verify(sp, c)
+        b, _ = run_verify(sp, c0)
+        np.testing.assert_array_equal(a[:n_q], b[:n_q])          # sequence 0: same tree, same bits
+        assert not np.array_equal(a[n_q:], b[n_q:])
+        if dtype == "bf16" and d == 128:
+            q, k, v = dev(c.q, dtype), dev(c.k, dtype), dev(c.v, dtype)
+            out = torch.empty_like(q)
+            sp.verify_attn_static(q, k, v, c.cu_seqlens, dev(trees), n_q, out)
+            torch.cuda.synchronize()
+            np.testing.assert_array_equal(host(out), a)
+
+
 @pytest.mark.parametrize("dtype,Hq,Hkv,d", SHAPES)
 def test_draft_windows_and_layouts(sp, oracle, dtype, Hq, Hkv, d):
     cfg = _cfg(dtype, Hq, Hkv, d)

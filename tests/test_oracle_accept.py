@@ -137,3 +137,27 @@ def test_accept_step_planted_prefixes(oracle):
         assert r["accept_len"][0] == a and r["bonus_id"][0] == c.planted_ids[a]
         # tau convention: tokens generated per target call = accepted + 1 bonus
         assert r["accept_len"][0] + 1 == a + 1
+
+
+def test_one_tree_per_sequence_walks_each_tree(oracle):
+    """parent [B, n_q]: the walk of sequence b follows tree b; a greedy replay written here from
+    the rule (children of the current node in ascending index, first token match) agrees."""
+    rng = np.random.default_rng(11)
+    B, V = 4, 6
+    trees = np.stack([wl.pruned_tree(20 + i, 10, (3, 2, 2)) for i in range(B)])
+    n_q = trees.shape[1]
+    for trial in range(50):
+        target = rng.integers(0, V, size=B * (n_q + 1)).astype(np.int32)
+        draft = rng.integers(0, V, size=B * n_q).astype(np.int32)
+        alen, path, bonus = oracle.accept(target, draft, trees, B, n_q)
+        for b in range(B):
+            t, d, par = target[b * (n_q + 1):(b + 1) * (n_q + 1)], draft[b * n_q:(b + 1) * n_q], trees[b]
+            cur, walked = -1, []
+            while True:
+                kids = [j for j in range(n_q) if par[j] == cur and d[j] == t[cur + 1]]
+                if not kids:
+                    break
+                cur = kids[0]
+                walked.append(cur)
+            assert alen[b] == len(walked) and list(path[b][:len(walked)]) == walked
+            assert bonus[b] == t[cur + 1]

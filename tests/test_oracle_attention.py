@@ -326,3 +326,25 @@ def test_c1_config_shapes_and_full_size_pin(oracle):
     out, _ = oracle.verify_attn(v.q, v.k, v.v, v.cu_seqlens, None, 4)
     ref = sdpa_dense(v.q, v.k, v.v, dense_verify_mask(512, 4, None), 1.0 / 8.0)
     np.testing.assert_allclose(out, ref, rtol=0, atol=1e-13)
+
+
+def test_one_tree_per_sequence_is_the_per_sequence_result(oracle):
+    """parent [B, n_q]: sequence b is verified with tree b.  Equal rows reproduce the shared-tree
+    call bit for bit; different rows reproduce, sequence by sequence, a single-sequence call with
+    that tree (and differ from the shared-tree result where the trees differ)."""
+    cfg = wl.Config("T", "f32", 4, 2, 64, 1, None, 8, 4, False, 64, 128)
+    lay = (((wl.TEXT, 37),), ((wl.TEXT, 5),), ((wl.TEXT, 60),))
+    trees = np.stack([wl.pruned_tree(i, 9, (3, 2, 2)) for i in range(3)])
+    n_q = trees.shape[1]
+    c = wl.verify_case(cfg, seed=4, layouts=lay, n_q=n_q, parent=None)
+    shared, shared_lse = oracle.verify_attn(c.q, c.k, c.v, c.cu_seqlens, trees[0], n_q)
+    same, same_lse = oracle.verify_attn(c.q, c.k, c.v, c.cu_seqlens, np.stack([trees[0]] * 3), n_q)
+    np.testing.assert_array_equal(shared, same)
+    np.testing.assert_array_equal(shared_lse, same_lse)
+    own, _ = oracle.verify_attn(c.q, c.k, c.v, c.cu_seqlens, trees, n_q)
+    cu = c.cu_seqlens
+    for b in range(3):
+        one, _ = oracle.verify_attn(c.q[b * n_q:(b + 1) * n_q], c.k[cu[b]:cu[b + 1]], c.v[cu[b]:cu[b + 1]],
+                                    [0, cu[b + 1] - cu[b]], trees[b], n_q)
+        np.testing.assert_array_equal(own[b * n_q:(b + 1) * n_q], one)
+    assert not np.array_equal(own[n_q:], shared[n_q:])

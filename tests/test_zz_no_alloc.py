@@ -37,7 +37,7 @@ def _both(sp, c):
     ref_out, ref_lse = sp.verify_attn(q, k, v, c.cu_seqlens, par, c.n_q)
     out = torch.full_like(q, float("nan"))
     lse = torch.full(q.shape[:2], float("nan"), dtype=torch.float32, device=q.device)
-    desc = b.AttnDesc(b.SPARROW_BF16, q.shape[1], k.shape[1], q.shape[2], 0.0, k.stride(0), k.stride(1))
+    desc = b.AttnDesc(b.SPARROW_BF16, q.shape[1], k.shape[1], q.shape[2], 0.0, k.stride(0), k.stride(1), 0)
     cu = np.ascontiguousarray(c.cu_seqlens, dtype=np.int32)
     rc = b.lib.sparrow_verify_attn_static(
         ctypes.byref(desc), b._ptr(q), b._ptr(k), b._ptr(v),
