@@ -400,6 +400,26 @@ int sparrow_stream_read(const void *dev_ptr, size_t bytes, void *sink, void *hip
 int sparrow_stream_read_shape(const void *dev_ptr, size_t bytes, void *sink, int32_t workgroups,
                               int32_t loads_in_flight, int32_t regions, void *hip_stream);
 
+/*
+ * Debug aids: synchronous checks of the device-resident preconditions that the entry points
+ * above cannot check without a device read.  The arrays may live in device memory (they are
+ * copied to the host on hip_stream, which is synchronised) or in ordinary host memory (read in
+ * place; this also works on a machine without a GPU).  SPARROW_OK, or SPARROW_ERR_INVALID_ARG with
+ * sparrow_last_error() naming the first offending entry.  Not for the hot path.
+ *
+ * sparrow_debug_validate_parent: every tree satisfies parent[i] in [-1, i) (nodes numbered so
+ *   that a parent precedes its children; the ancestor walks of sparrow_verify_attn and the
+ *   acceptance walks then terminate).  parent [n_q] with parent_stride 0 (B is ignored), or
+ *   [B, parent_stride] with parent_stride >= n_q.
+ * sparrow_debug_validate_text_idx: for every sequence b, text_idx[cu_text[b] .. cu_text[b+1]) is
+ *   strictly ascending and inside [0, cu_seqlens[b+1] - cu_seqlens[b]), and holds at least one
+ *   entry.  cu_seqlens, cu_text: host int32 [B+1].
+ */
+int sparrow_debug_validate_parent(const int32_t *parent, int32_t parent_stride, int32_t B,
+                                  int32_t n_q, void *hip_stream);
+int sparrow_debug_validate_text_idx(const int32_t *text_idx, const int32_t *cu_seqlens,
+                                    const int32_t *cu_text, int32_t B, void *hip_stream);
+
 /* Thread-local description of the last error on this thread; "" if none. */
 const char *sparrow_last_error(void);
 

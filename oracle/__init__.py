@@ -25,10 +25,20 @@ _dp = ctypes.POINTER(ctypes.c_double)
 _ip = ctypes.POINTER(ctypes.c_int32)
 
 
+# SPARROW_ORACLE_SANITIZE=1 (set by tests/test_oracle_sanitized.py for a child process that has the
+# AddressSanitizer runtime preloaded): a second library built with -fsanitize=address,undefined,
+# so that an out-of-bounds access or undefined behaviour in the oracle aborts the run.
+_SANITIZE = os.environ.get("SPARROW_ORACLE_SANITIZE") == "1"
+if _SANITIZE:
+    _LIB = os.path.join(_HERE, "libsparrow_oracle_san.so")
+
+
 def build(force: bool = False) -> str:
     """Compile the oracle with gcc (-O2, OpenMP).  Returns the library path."""
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
-        cmd = ["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-std=c99", "-Wall", "-Wextra",
+        opt = ["-O1", "-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=all",
+               "-fno-omit-frame-pointer"] if _SANITIZE else ["-O2"]
+        cmd = ["gcc", *opt, "-fopenmp", "-fPIC", "-shared", "-std=c99", "-Wall", "-Wextra",
                "-o", _LIB, _SRC, "-lm"]
         subprocess.run(cmd, check=True)
     return _LIB

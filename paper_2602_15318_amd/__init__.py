@@ -8,7 +8,8 @@ __all__ = ["SparrowError", "accept", "accept_workspace_bytes", "draft_window_att
            "library_path", "verify_attn", "verify_attn_workspace_bytes", "version", "AttnDesc",
            "lib", "hsr_fc", "draft_qkv_append", "kv_commit", "accept_sample",
            "accept_sample_workspace_bytes", "draft_topk", "TreePool", "stream_read",
-           "verify_attn_static", "STATIC_WS_BYTES"]
+           "verify_attn_static", "STATIC_WS_BYTES", "debug_validate_parent",
+           "debug_validate_text_idx"]
 
 
 def __getattr__(name):

@@ -99,6 +99,10 @@ def _load() -> ctypes.CDLL:
                                       ctypes.c_int32, vp, vp]
     L.sparrow_tree_select.restype = ctypes.c_int
     L.sparrow_tree_select.argtypes = [vp, vp, vp, ctypes.c_int32, ctypes.c_int32, vp, vp, vp, vp]
+    L.sparrow_debug_validate_parent.restype = ctypes.c_int
+    L.sparrow_debug_validate_parent.argtypes = [vp, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, vp]
+    L.sparrow_debug_validate_text_idx.restype = ctypes.c_int
+    L.sparrow_debug_validate_text_idx.argtypes = [vp, i32p, i32p, ctypes.c_int32, vp]
     L.sparrow_stream_read.restype = ctypes.c_int
     L.sparrow_stream_read.argtypes = [vp, ctypes.c_size_t, vp, vp]
     L.sparrow_stream_read_shape.restype = ctypes.c_int
@@ -459,6 +463,23 @@ class TreePool:
                                        total, _ptr(parent), _ptr(ids), _ptr(pidx),
                                        _stream_ptr(stream)))
         return parent, ids, pidx
+
+
+def debug_validate_parent(parent: torch.Tensor, n_q: int, B: int = 1, stream=None) -> None:
+    """sparrow_debug_validate_parent on a device tensor [n_q] or [B, n_q]: raises SparrowError
+    naming the first entry outside [-1, i).  Synchronises the stream."""
+    _check(lib.sparrow_debug_validate_parent(_ptr(parent), _parent_stride(parent, n_q, B), B, int(n_q),
+                                             _stream_ptr(stream)))
+
+
+def debug_validate_text_idx(text_idx: torch.Tensor, cu_seqlens, cu_text, stream=None) -> None:
+    """sparrow_debug_validate_text_idx on a device tensor: per sequence strictly ascending,
+    in range, not empty.  Synchronises the stream."""
+    cu, ct = _host_i32(cu_seqlens), _host_i32(cu_text)
+    if text_idx.dtype != torch.int32 or not text_idx.is_contiguous():
+        raise ValueError("text_idx must be a contiguous int32 tensor")
+    _check(lib.sparrow_debug_validate_text_idx(_ptr(text_idx), _i32p(cu), _i32p(ct), cu.shape[0] - 1,
+                                               _stream_ptr(stream)))
 
 
 def stream_read(t: torch.Tensor, sink: torch.Tensor, stream=None, shape=None) -> None:

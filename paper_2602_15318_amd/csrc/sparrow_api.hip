@@ -7,6 +7,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <vector>
 
 #include "../../include/sparrow.h"
 #include "accept.hpp"
@@ -283,6 +284,75 @@ int sparrow_stream_read_shape(const void *dev_ptr, size_t bytes, void *sink, int
 
 int sparrow_stream_read(const void *dev_ptr, size_t bytes, void *sink, void *hip_stream) {
   return sparrow_stream_read_shape(dev_ptr, bytes, sink, 1024, 8, 0, hip_stream);
+}
+
+// ------------------------------------------------------------------ debug aids
+// Host copy of `n` int32 at `p`, wherever they live.  Memory the runtime does not know (plain host
+// memory; every pointer on a machine without a device) is read in place.
+static int host_copy_i32(const int32_t *p, size_t n, hipStream_t st, std::vector<int32_t> *out) {
+  out->resize(n);
+  if (n == 0) return SPARROW_OK;
+  hipPointerAttribute_t attr;
+  const hipError_t qa = hipPointerGetAttributes(&attr, p);
+  if (qa != hipSuccess) (void)hipGetLastError();          // unknown pointer: clear the sticky error
+  const bool on_device = qa == hipSuccess && (attr.type == hipMemoryTypeDevice || attr.type == hipMemoryTypeManaged);
+  if (!on_device) {
+    memcpy(out->data(), p, n * sizeof(int32_t));
+    return SPARROW_OK;
+  }
+  hipError_t e = hipMemcpyAsync(out->data(), p, n * sizeof(int32_t), hipMemcpyDeviceToHost, st);
+  if (e == hipSuccess) e = hipStreamSynchronize(st);
+  if (e != hipSuccess) return fail(SPARROW_ERR_DEVICE, "copy to the host: %s", hipGetErrorString(e));
+  return SPARROW_OK;
+}
+
+int sparrow_debug_validate_parent(const int32_t *parent, int32_t parent_stride, int32_t B,
+                                  int32_t n_q, void *hip_stream) {
+  g_err[0] = 0;
+  if (n_q < 0 || n_q > SPARROW_MAX_NQ) return fail(SPARROW_ERR_INVALID_ARG, "n_q = %d (0..%d)", n_q, SPARROW_MAX_NQ);
+  if (!parent || n_q == 0) return SPARROW_OK;             // NULL = chain: nothing to check
+  if (parent_stride != 0 && (parent_stride < n_q || B < 0 || B > SPARROW_MAX_BATCH))
+    return fail(SPARROW_ERR_INVALID_ARG, "parent_stride = %d (0 or >= n_q = %d), B = %d", parent_stride, n_q, B);
+  const int trees = parent_stride == 0 ? 1 : B;
+  if (trees == 0) return SPARROW_OK;
+  const size_t n = parent_stride == 0 ? (size_t)n_q : (size_t)(trees - 1) * parent_stride + n_q;
+  std::vector<int32_t> h;
+  if (int rc = host_copy_i32(parent, n, (hipStream_t)hip_stream, &h)) return rc;
+  for (int b = 0; b < trees; ++b)
+    for (int i = 0; i < n_q; ++i) {
+      const int32_t pi = h[(size_t)b * parent_stride + i];
+      if (pi < -1 || pi >= i)
+        return fail(SPARROW_ERR_INVALID_ARG, "tree %d: parent[%d] = %d is outside [-1, %d)", b, i, pi, i);
+    }
+  return SPARROW_OK;
+}
+
+int sparrow_debug_validate_text_idx(const int32_t *text_idx, const int32_t *cu_seqlens,
+                                    const int32_t *cu_text, int32_t B, void *hip_stream) {
+  g_err[0] = 0;
+  if (B < 0 || B > SPARROW_MAX_BATCH) return fail(SPARROW_ERR_INVALID_ARG, "B = %d (0..%d)", B, SPARROW_MAX_BATCH);
+  if (B == 0) return SPARROW_OK;
+  if (!text_idx || !cu_seqlens || !cu_text) return fail(SPARROW_ERR_INVALID_ARG, "NULL pointer among text_idx/cu_seqlens/cu_text");
+  if (cu_text[0] < 0 || cu_seqlens[0] < 0) return fail(SPARROW_ERR_INVALID_ARG, "cu_text[0] and cu_seqlens[0] must be >= 0");
+  for (int b = 0; b < B; ++b)
+    if (cu_text[b + 1] <= cu_text[b] || cu_seqlens[b + 1] <= cu_seqlens[b])
+      return fail(SPARROW_ERR_INVALID_ARG, "sequence %d: %d text positions in %d tokens", b,
+                  cu_text[b + 1] - cu_text[b], cu_seqlens[b + 1] - cu_seqlens[b]);
+  std::vector<int32_t> h;
+  if (int rc = host_copy_i32(text_idx + cu_text[0], (size_t)(cu_text[B] - cu_text[0]), (hipStream_t)hip_stream, &h)) return rc;
+  for (int b = 0; b < B; ++b) {
+    const int len = cu_seqlens[b + 1] - cu_seqlens[b];
+    int prev = -1;
+    for (int j = cu_text[b]; j < cu_text[b + 1]; ++j) {
+      const int32_t t = h[(size_t)(j - cu_text[0])];
+      if (t <= prev || t >= len)
+        return fail(SPARROW_ERR_INVALID_ARG,
+                    "sequence %d: text_idx[%d] = %d is not above its predecessor %d or not below the sequence's %d tokens",
+                    b, j, t, prev, len);
+      prev = t;
+    }
+  }
+  return SPARROW_OK;
 }
 
 const char *sparrow_last_error(void) { return g_err; }

@@ -224,3 +224,33 @@ def test_stream_read_argument_validation(lib):
     assert call(P, 40) == INVALID                          # not a multiple of 16
     assert call(ctypes.c_void_p(0x10004), 64) == INVALID   # misaligned
     assert call(P, 64, sink=None) == INVALID
+
+
+def test_debug_validators_on_host_arrays(lib):
+    """The synchronous precondition checks, given ordinary host memory (no device needed)."""
+    ip = ctypes.POINTER(ctypes.c_int32)
+    vp = lambda a: ctypes.c_void_p(a.ctypes.data)      # noqa: E731
+    good = np.array([-1, 0, 0, 1, 3, -1], dtype=np.int32)
+    assert lib.sparrow_debug_validate_parent(vp(good), 0, 1, 6, None) == OK
+    assert lib.sparrow_debug_validate_parent(None, 0, 1, 6, None) == OK          # NULL = chain
+    for bad_at, val in ((0, 0), (2, 2), (4, 7), (3, -2)):
+        bad = good.copy()
+        bad[bad_at] = val
+        assert lib.sparrow_debug_validate_parent(vp(bad), 0, 1, 6, None) == INVALID
+        assert f"parent[{bad_at}] = {val}".encode() in lib.sparrow_last_error()
+    trees = np.full((3, 8), 99, dtype=np.int32)            # stride 8 > n_q = 6: padding is ignored
+    trees[:, :6] = good
+    assert lib.sparrow_debug_validate_parent(vp(trees), 8, 3, 6, None) == OK
+    trees[2, 5] = 5
+    assert lib.sparrow_debug_validate_parent(vp(trees), 8, 3, 6, None) == INVALID
+    assert b"tree 2" in lib.sparrow_last_error()
+    assert lib.sparrow_debug_validate_parent(vp(trees), 4, 3, 6, None) == INVALID    # stride < n_q
+    cu = np.array([0, 10, 14], dtype=np.int32)
+    ct = np.array([0, 3, 5], dtype=np.int32)
+    tix = np.array([0, 4, 9, 1, 3], dtype=np.int32)
+    call = lambda t, c=cu, x=ct: lib.sparrow_debug_validate_text_idx(                # noqa: E731
+        vp(t), c.ctypes.data_as(ip), x.ctypes.data_as(ip), 2, None)
+    assert call(tix) == OK
+    for bad in ([0, 4, 10, 1, 3], [0, 4, 4, 1, 3], [4, 0, 9, 1, 3], [0, 4, 9, 1, 4], [-1, 4, 9, 1, 3]):
+        assert call(np.array(bad, dtype=np.int32)) == INVALID, bad
+    assert call(tix, x=np.array([0, 3, 3], dtype=np.int32)) == INVALID               # empty text domain

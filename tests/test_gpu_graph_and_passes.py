@@ -184,3 +184,24 @@ def test_stream_read_runs_and_leaves_its_input_alone(sp):
     sp.stream_read(w, sink)
     torch.cuda.synchronize()
     assert int(sink.item()) == -1
+
+
+def test_debug_validators_on_device_arrays(sp):
+    """The synchronous precondition checks on device-resident arrays."""
+    import torch
+    par = wl.pruned_tree(0, 30, (4, 3, 2, 2))
+    d_par = torch.from_numpy(par).cuda()
+    sp.debug_validate_parent(d_par, 30)
+    trees = torch.from_numpy(np.stack([wl.pruned_tree(i, 30, (4, 3, 2, 2)) for i in range(4)])).cuda()
+    sp.debug_validate_parent(trees, 30, B=4)
+    trees[3, 17] = 17
+    with pytest.raises(sp.SparrowError) as e:
+        sp.debug_validate_parent(trees, 30, B=4)
+    assert e.value.code == -1 and "tree 3: parent[17] = 17" in str(e.value)
+    c = wl.draft_case(wl.C4, 0)
+    tix = torch.from_numpy(c.text_idx).cuda()
+    sp.debug_validate_text_idx(tix, c.cu_seqlens, c.cu_text)
+    tix[int(c.cu_text[5]) + 1] = 10 ** 6
+    with pytest.raises(sp.SparrowError) as e:
+        sp.debug_validate_text_idx(tix, c.cu_seqlens, c.cu_text)
+    assert e.value.code == -1 and "sequence 5" in str(e.value)
