@@ -61,6 +61,9 @@ def _load():
         _lib.oracle_rope_table.restype = None
         _lib.oracle_kv_commit.restype = None
         _lib.oracle_accept_sample.restype = ctypes.c_int
+        _lib.oracle_accept_sample_q.restype = ctypes.c_int
+        _lib.oracle_philox4x32_10.restype = None
+        _lib.oracle_philox_uniforms.restype = None
         _lib.oracle_topk_logprob.restype = None
         _lib.oracle_tree_expand.restype = ctypes.c_int
         _lib.oracle_tree_select.restype = ctypes.c_int
@@ -311,6 +314,60 @@ def accept_sample(lg, draft_ids, parent, B: int, n_q: int, temperature: float, u
     if rc != 0:
         raise ValueError(f"oracle_accept_sample: bad arguments ({rc})")
     return alen, path, bonus, margin
+
+
+def accept_sample_q(lg, draft_ids, parent, B: int, n_q: int, temperature: float, draft_q,
+                    u_accept, u_bonus):
+    """Stochastic acceptance against a sampled draft: draft_q [B*(n_q+1), V] holds, per logit row,
+    the distribution its children's tokens were drawn from.  Returns (accept_len [B],
+    accept_path [B, n_q], bonus_id [B], margin [B]).  parent [n_q], [B, n_q] or None."""
+    lib = _load()
+    lg, dq = _f64(lg), _f64(draft_q)
+    V = lg.shape[1]
+    assert lg.shape[0] == B * (n_q + 1) and dq.shape == lg.shape
+    dr = _i32(draft_ids)
+    if parent is not None and np.ndim(parent) == 2:      # one tree per sequence: per-sequence walks
+        par2 = _i32(parent)
+        assert par2.shape == (B, n_q)
+        ua2, ub2 = np.asarray(u_accept).reshape(B, n_q), np.asarray(u_bonus).reshape(B)
+        parts = [accept_sample_q(lg[b * (n_q + 1):(b + 1) * (n_q + 1)], dr[b * n_q:(b + 1) * n_q], par2[b],
+                                 1, n_q, temperature, dq[b * (n_q + 1):(b + 1) * (n_q + 1)],
+                                 ua2[b:b + 1], ub2[b:b + 1]) for b in range(B)]
+        return tuple(np.concatenate([p[i] for p in parts]) for i in range(4))
+    par = None if parent is None else _i32(parent)
+    ua, ub = _f64(u_accept).reshape(B, max(n_q, 0)), _f64(u_bonus)
+    alen = np.empty(B, dtype=np.int32)
+    path = np.empty((B, n_q), dtype=np.int32)
+    bonus = np.empty(B, dtype=np.int32)
+    margin = np.empty(B, dtype=np.float64)
+    rc = lib.oracle_accept_sample_q(_ptr(lg, _dp), _ptr(dr, _ip), _ptr(par, _ip), ctypes.c_int(B),
+                                    ctypes.c_int(n_q), ctypes.c_int64(V), ctypes.c_double(temperature),
+                                    _ptr(dq, _dp), _ptr(ua, _dp), _ptr(ub, _dp), _ptr(alen, _ip),
+                                    _ptr(path, _ip), _ptr(bonus, _ip), _ptr(margin, _dp))
+    if rc != 0:
+        raise ValueError(f"oracle_accept_sample_q: bad arguments ({rc})")
+    return alen, path, bonus, margin
+
+
+def philox4x32_10(counter, key) -> np.ndarray:
+    """One block of Philox4x32-10: counter 4 x uint32, key 2 x uint32 -> 4 x uint32."""
+    c = np.ascontiguousarray(counter, dtype=np.uint32)
+    k = np.ascontiguousarray(key, dtype=np.uint32)
+    assert c.shape == (4,) and k.shape == (2,)
+    out = np.empty(4, dtype=np.uint32)
+    up = ctypes.POINTER(ctypes.c_uint32)
+    _load().oracle_philox4x32_10(c.ctypes.data_as(up), k.ctypes.data_as(up), out.ctypes.data_as(up))
+    return out
+
+
+def philox_uniforms(seed: int, offset: int, B: int, n_q: int):
+    """The uniforms of a call that leaves their generation to the library: (u_accept [B, n_q],
+    u_bonus [B]) float64, each a multiple of 2^-24 in [0, 1)."""
+    ua = np.empty((B, max(n_q, 0)), dtype=np.float64)
+    ub = np.empty(B, dtype=np.float64)
+    _load().oracle_philox_uniforms(ctypes.c_uint64(seed), ctypes.c_uint64(offset), ctypes.c_int(B),
+                                   ctypes.c_int(n_q), _ptr(ua, _dp), _ptr(ub, _dp))
+    return ua, ub
 
 
 def accept_sample_step(hidden, lm_head, draft_ids, parent, B: int, n_q: int, temperature: float,

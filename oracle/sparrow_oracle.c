@@ -440,6 +440,150 @@ int oracle_accept_sample(const double *logits, const int32_t *draft_ids, const i
 }
 
 /* ------------------------------------------------------------------------
+ * Stochastic acceptance against a SAMPLED draft (temperature > 0): the
+ * speculative-sampling rule whose distribution guarantee the paper relies on
+ * (Related Work, first paragraph), for a draft that draws its proposals from
+ * a distribution q instead of proposing them with certainty, extended to
+ * several sibling proposals drawn independently from the same q (multi-round
+ * rejection of the tree-speculation line of work):
+ *   at the current node, p = softmax(logits / T) of the node's row and q =
+ *   the draft's distribution over the children's tokens (row of draft_q);
+ *   the residual is R = p with mass S = 1;
+ *   children are tried in increasing node index; child j with token x is
+ *   accepted with probability min(1, (R[x] / S) / q[x]), i.e. if
+ *       R[x] > 0  and  u_accept[j] * q[x] * S <= R[x];
+ *   on a rejection the residual becomes R[v] <- max(R[v] - S q[v], 0) for
+ *   every v, S <- sum_v R[v]   (the normalised max(p - q, 0) of the rule);
+ *   an accepted child becomes the current node (fresh p, q, R);
+ *   when no child is accepted, or at a leaf, the bonus token is drawn from
+ *   the residual by inverse CDF in vocabulary order:
+ *       bonus = min { t : sum_{v <= t} R[v] >= u_bonus * S }.
+ * With children drawn i.i.d. from q the first emitted token is distributed
+ * exactly as p (pinned by Monte Carlo and closed forms in the tests).
+ *
+ * draft_q [B*(n_q+1), V]: row r = distribution the children of row r were
+ * drawn from (row 0 of a sequence = last accepted token, row 1+i = node i);
+ * rows of leaves are not read.  Other arguments, outputs and margin as
+ * oracle_accept_sample; the margin of an acceptance test is
+ * |u q[x] S - R[x]| / S.
+ * ------------------------------------------------------------------------ */
+int oracle_accept_sample_q(const double *logits, const int32_t *draft_ids, const int32_t *parent,
+                           int B, int n_q, int64_t V, double temperature, const double *draft_q,
+                           const double *u_accept, const double *u_bonus, int32_t *accept_len,
+                           int32_t *accept_path, int32_t *bonus_id, double *margin)
+{
+    if (!(temperature > 0.0)) return -2;
+    for (int i = 0; parent && i < n_q; ++i)
+        if (parent[i] < -1 || parent[i] >= i) return -1;
+    double *R = (double *)malloc(sizeof(double) * (size_t)V);
+    for (int b = 0; b < B; ++b) {
+        const int32_t *dr = draft_ids + (int64_t)b * n_q;
+        int32_t *path = accept_path + (int64_t)b * n_q;
+        for (int i = 0; i < n_q; ++i) path[i] = -1;
+        int cur = -1, len = 0;
+        double worst = INFINITY;
+        for (;;) {
+            const int64_t row = (int64_t)b * (n_q + 1) + cur + 1;
+            const double *lr = logits + row * V;
+            const double *q = draft_q + row * V;
+            double mx = -INFINITY, Z = 0.0;
+            for (int64_t v = 0; v < V; ++v) if (lr[v] / temperature > mx) mx = lr[v] / temperature;
+            for (int64_t v = 0; v < V; ++v) { R[v] = exp(lr[v] / temperature - mx); Z += R[v]; }
+            for (int64_t v = 0; v < V; ++v) R[v] /= Z;
+            double S = 1.0;
+            int next = -1;
+            for (int j = 0; j < n_q && next < 0; ++j) {
+                const int pj = parent ? parent[j] : j - 1;
+                if (pj != cur) continue;
+                const int32_t x = dr[j];
+                if (x < 0 || x >= V) continue;
+                const double lhs = u_accept[(int64_t)b * n_q + j] * q[x] * S;
+                const double gap = fabs(lhs - R[x]) / S;
+                if (gap < worst) worst = gap;
+                if (R[x] > 0.0 && lhs <= R[x]) { next = j; break; }
+                double S_new = 0.0;                     /* rejected: R <- max(R - S q, 0) */
+                for (int64_t v = 0; v < V; ++v) {
+                    const double r = R[v] - S * q[v];
+                    R[v] = r > 0.0 ? r : 0.0;
+                    S_new += R[v];
+                }
+                S = S_new;
+            }
+            if (next >= 0) { path[len++] = next; cur = next; continue; }
+            const double target = u_bonus[b] * S;
+            double cdf = 0.0;
+            int64_t pick = -1, last_pos = -1;
+            for (int64_t v = 0; v < V; ++v) {
+                if (R[v] <= 0.0) continue;
+                last_pos = v;
+                const double before = cdf;
+                cdf += R[v];
+                if (cdf >= target) {
+                    pick = v;
+                    double g = (cdf - target) / S;
+                    if (before > 0.0 && (target - before) / S < g) g = (target - before) / S;
+                    if (g < worst) worst = g;
+                    break;
+                }
+            }
+            if (pick < 0) pick = last_pos;          /* rounding left the sum a hair below target */
+            bonus_id[b] = (int32_t)(pick < 0 ? 0 : pick);
+            break;
+        }
+        accept_len[b] = len;
+        if (margin) margin[b] = worst;
+    }
+    free(R);
+    return 0;
+}
+
+/* ------------------------------------------------------------------------
+ * Counter-based random numbers for the acceptance tests: Philox4x32 with 10
+ * rounds (Salmon, Moraes, Dror, Shaw: "Parallel random numbers: as easy as
+ * 1, 2, 3", SC'11).  One round maps the counter (c0, c1, c2, c3) with round
+ * key (k0, k1) to (hi(M1 c2) ^ c1 ^ k0, lo(M1 c2), hi(M0 c0) ^ c3 ^ k1,
+ * lo(M0 c0)) with the multipliers M0 = 0xD2511F53, M1 = 0xCD9E8D57; the key
+ * grows by the Weyl constants (0x9E3779B9, 0xBB67AE85) after every round.
+ * Uniforms: the top 24 bits of a 32-bit output, times 2^-24, in [0, 1).
+ *   u_accept[b][j] = first output word of counter (offset lo, offset hi, b, j),
+ *   u_bonus[b]     = first output word of counter (offset lo, offset hi, b, 0xFFFFFFFF),
+ * both under the key (seed lo, seed hi).
+ * ------------------------------------------------------------------------ */
+void oracle_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4])
+{
+    uint32_t c0 = ctr[0], c1 = ctr[1], c2 = ctr[2], c3 = ctr[3];
+    uint32_t k0 = key[0], k1 = key[1];
+    for (int round = 0; round < 10; ++round) {
+        const uint64_t p0 = (uint64_t)0xD2511F53u * c0;
+        const uint64_t p1 = (uint64_t)0xCD9E8D57u * c2;
+        const uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
+        const uint32_t n1 = (uint32_t)p1;
+        const uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+        const uint32_t n3 = (uint32_t)p0;
+        c0 = n0; c1 = n1; c2 = n2; c3 = n3;
+        k0 += 0x9E3779B9u;
+        k1 += 0xBB67AE85u;
+    }
+    out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+void oracle_philox_uniforms(uint64_t seed, uint64_t offset, int B, int n_q, double *u_accept,
+                            double *u_bonus)
+{
+    const uint32_t key[2] = {(uint32_t)seed, (uint32_t)(seed >> 32)};
+    for (int b = 0; b < B; ++b) {
+        for (int j = 0; j <= n_q; ++j) {
+            const uint32_t ctr[4] = {(uint32_t)offset, (uint32_t)(offset >> 32), (uint32_t)b,
+                                     j < n_q ? (uint32_t)j : 0xFFFFFFFFu};
+            uint32_t out[4];
+            oracle_philox4x32_10(ctr, key, out);
+            const double u = (double)(out[0] >> 8) * (1.0 / 16777216.0);
+            if (j < n_q) u_accept[(int64_t)b * n_q + j] = u; else u_bonus[b] = u;
+        }
+    }
+}
+
+/* ------------------------------------------------------------------------
  * Dynamic draft tree (Experiment section: "dynamic tree structure",
  * configuration total tokens - depth - width, e.g. 30-4-8).  The paper names
  * the configuration and not the procedure; reading taken: the best-first

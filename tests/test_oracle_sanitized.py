@@ -9,6 +9,7 @@ import sys
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 PINS = ["tests/test_oracle_attention.py", "tests/test_oracle_accept.py", "tests/test_oracle_accept_sample.py",
+        "tests/test_oracle_accept_sample_q.py",
         "tests/test_oracle_tree.py", "tests/test_oracle_commit.py", "tests/test_oracle_hsr.py"]
 
 
