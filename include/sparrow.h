@@ -265,6 +265,39 @@ int sparrow_accept_sample_trees(int32_t dtype, const void *hidden_rows, const vo
                                 void *hip_stream);
 
 /*
+ * Stochastic acceptance against a SAMPLED draft, and with uniforms generated by the library:
+ * the speculative-sampling rule behind the paper's losslessness at temperature > 0 (Related
+ * Work: speculative sampling's distribution guarantee; "Temp = 1" blocks of the result tables)
+ * for a draft that draws its proposals from a distribution q instead of proposing them with
+ * certainty.  draft_probs holds, for every logit row r, the distribution the tokens of row r's
+ * children were drawn from (independently, if there are several).  With p = softmax(logits /
+ * temperature) of the current row, residual R = p and S = 1: child j with token x is accepted if
+ * R[x] > 0 and u_accept[b][j] * q[x] * S <= R[x], i.e. with probability min(1, (R[x]/S) / q[x]);
+ * on a rejection R[v] <- max(R[v] - S q[v], 0) for all v and S <- sum R (the normalised
+ * max(p - q, 0)); the accepted child becomes the current node; when no child is accepted, or at
+ * a leaf, bonus = min { t : sum_{v<=t} R[v] >= u_bonus[b] * S }.  The first emitted token is
+ * then distributed exactly as p.
+ *
+ *  draft_probs dev float [B*(n_q+1), vocab], 16-byte aligned, rows of leaves are not read;
+ *              NULL = the deterministic-children rule of sparrow_accept_sample
+ *  u_accept, u_bonus   both dev as in sparrow_accept_sample, or both NULL: the uniforms are then
+ *              generated by Philox4x32-10 (Salmon et al., SC'11) under the key (seed low word,
+ *              seed high word): node j of sequence b takes the first output word of the counter
+ *              (offset low, offset high, b, j), the bonus draw that of (offset low, offset high,
+ *              b, 0xFFFFFFFF); uniform = (word >> 8) * 2^-24.  A caller advances `offset` by one
+ *              per step, so no step reuses a number.
+ *  parent, parent_stride   as sparrow_accept_trees;  workspace: sparrow_accept_sample_workspace()
+ *  A rejection costs one pass of one workgroup over the row's logits and draft probabilities.
+ */
+int sparrow_accept_sample_q(int32_t dtype, const void *hidden_rows, const void *lm_head,
+                            const int32_t *draft_ids, const int32_t *parent, int32_t parent_stride,
+                            int32_t B, int32_t n_q, int32_t hidden, int32_t vocab, float temperature,
+                            const float *draft_probs, const float *u_accept, const float *u_bonus,
+                            uint64_t seed, uint64_t offset, int32_t *accept_len,
+                            int32_t *accept_path, int32_t *bonus_id, void *workspace,
+                            size_t workspace_bytes, void *hip_stream);
+
+/*
  * Dynamic draft tree (Experiment section: dynamic tree structure with the
  * configuration "total tokens - depth - width", e.g. 30-4-8; the procedure is
  * not printed, the best-first expansion of the tree-speculation work the paper

@@ -463,9 +463,13 @@ int oracle_accept_sample(const double *logits, const int32_t *draft_ids, const i
  *
  * draft_q [B*(n_q+1), V]: row r = distribution the children of row r were
  * drawn from (row 0 of a sequence = last accepted token, row 1+i = node i);
- * rows of leaves are not read.  Other arguments, outputs and margin as
- * oracle_accept_sample; the margin of an acceptance test is
- * |u q[x] S - R[x]| / S.
+ * rows of leaves are not read.  Other arguments and outputs as
+ * oracle_accept_sample.  margin: the bonus draw as there (distance of u S to
+ * the CDF values around it, over S); an acceptance test compares two numbers
+ * that can both be tiny against S (a tail token has q[x] and p[x] ~ 1e-5), so
+ * its distance |u q[x] S - R[x]| is taken relative to the magnitudes that
+ * went into it: u q[x] S + p[x] + q[x] * (sum of the S of the rejections so
+ * far at this node) -- the scale on which rounding moves either side.
  * ------------------------------------------------------------------------ */
 int oracle_accept_sample_q(const double *logits, const int32_t *draft_ids, const int32_t *parent,
                            int B, int n_q, int64_t V, double temperature, const double *draft_q,
@@ -490,7 +494,7 @@ int oracle_accept_sample_q(const double *logits, const int32_t *draft_ids, const
             for (int64_t v = 0; v < V; ++v) if (lr[v] / temperature > mx) mx = lr[v] / temperature;
             for (int64_t v = 0; v < V; ++v) { R[v] = exp(lr[v] / temperature - mx); Z += R[v]; }
             for (int64_t v = 0; v < V; ++v) R[v] /= Z;
-            double S = 1.0;
+            double S = 1.0, S_spent = 0.0;              /* S_spent: sum of S over the rejections */
             int next = -1;
             for (int j = 0; j < n_q && next < 0; ++j) {
                 const int pj = parent ? parent[j] : j - 1;
@@ -498,9 +502,12 @@ int oracle_accept_sample_q(const double *logits, const int32_t *draft_ids, const
                 const int32_t x = dr[j];
                 if (x < 0 || x >= V) continue;
                 const double lhs = u_accept[(int64_t)b * n_q + j] * q[x] * S;
-                const double gap = fabs(lhs - R[x]) / S;
+                const double px = exp(lr[x] / temperature - mx) / Z;
+                const double scale = lhs + px + q[x] * S_spent;
+                const double gap = scale > 0.0 ? fabs(lhs - R[x]) / scale : 0.0;
                 if (gap < worst) worst = gap;
                 if (R[x] > 0.0 && lhs <= R[x]) { next = j; break; }
+                S_spent += S;
                 double S_new = 0.0;                     /* rejected: R <- max(R - S q, 0) */
                 for (int64_t v = 0; v < V; ++v) {
                     const double r = R[v] - S * q[v];

@@ -9,7 +9,7 @@ __all__ = ["SparrowError", "accept", "accept_workspace_bytes", "draft_window_att
            "lib", "hsr_fc", "draft_qkv_append", "kv_commit", "accept_sample",
            "accept_sample_workspace_bytes", "draft_topk", "TreePool", "stream_read",
            "verify_attn_static", "STATIC_WS_BYTES", "debug_validate_parent",
-           "debug_validate_text_idx"]
+           "debug_validate_text_idx", "accept_sample_q"]
 
 
 def __getattr__(name):

@@ -73,6 +73,12 @@ def _load() -> ctypes.CDLL:
                                               ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
                                               ctypes.c_int32, ctypes.c_float, vp, vp, vp, vp, vp, vp,
                                               ctypes.c_size_t, vp]
+    L.sparrow_accept_sample_q.restype = ctypes.c_int
+    L.sparrow_accept_sample_q.argtypes = [ctypes.c_int32, vp, vp, vp, vp, ctypes.c_int32,
+                                          ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
+                                          ctypes.c_int32, ctypes.c_float, vp, vp, vp,
+                                          ctypes.c_uint64, ctypes.c_uint64, vp, vp, vp, vp,
+                                          ctypes.c_size_t, vp]
     L.sparrow_hsr_fc.restype = ctypes.c_int
     L.sparrow_hsr_fc.argtypes = [ctypes.c_int32, vp, vp, vp, vp, vp, ctypes.c_int32, ctypes.c_int32,
                                  ctypes.c_int32, vp, vp]
@@ -403,6 +409,41 @@ def accept_sample(hidden_rows, lm_head, draft_ids, parent, B: int, n_q: int, tem
                                      _ptr(outputs["accept_path"]) if n_q > 0 else None,
                                      _ptr(outputs["bonus_id"]), _ptr(ws),
                                      0 if ws is None else ws.numel(), _stream_ptr(stream)))
+    return outputs
+
+
+def accept_sample_q(hidden_rows, lm_head, draft_ids, parent, B: int, n_q: int, temperature: float,
+                    draft_probs=None, u_accept=None, u_bonus=None, seed: int = 0, offset: int = 0,
+                    workspace=None, outputs=None, stream=None):
+    """sparrow_accept_sample_q: stochastic acceptance against a sampled draft (draft_probs float32
+    [B*(n_q+1), V], or None for the deterministic-children rule), with the caller's uniforms or,
+    if both are None, uniforms generated by the library from (seed, offset)."""
+    M, H = hidden_rows.shape
+    V = lm_head.shape[0]
+    if M != B * (n_q + 1) or lm_head.shape[1] != H:
+        raise ValueError("hidden_rows must be [B*(n_q+1), H] and lm_head [V, H]")
+    if not hidden_rows.is_contiguous() or not lm_head.is_contiguous() or lm_head.dtype != hidden_rows.dtype:
+        raise ValueError("hidden_rows and lm_head must be contiguous and of one dtype")
+    for t in (u_accept, u_bonus, draft_probs):
+        if t is not None and (t.dtype != torch.float32 or not t.is_contiguous()):
+            raise ValueError("u_accept, u_bonus and draft_probs must be contiguous float32 tensors")
+    if draft_probs is not None and tuple(draft_probs.shape) != (M, V):
+        raise ValueError("draft_probs must be [B*(n_q+1), V]")
+    dev = hidden_rows.device
+    code = _dtype_code(hidden_rows)
+    ws = _workspace(accept_sample_workspace_bytes(code, B, n_q, H, V), dev, workspace)
+    if outputs is None:
+        outputs = {"accept_len": torch.empty(B, dtype=torch.int32, device=dev),
+                   "accept_path": torch.empty((B, n_q), dtype=torch.int32, device=dev),
+                   "bonus_id": torch.empty(B, dtype=torch.int32, device=dev)}
+    _check(lib.sparrow_accept_sample_q(code, _ptr(hidden_rows), _ptr(lm_head), _ptr(draft_ids),
+                                       _ptr(parent), _parent_stride(parent, n_q, B), B, n_q, H, V,
+                                       float(temperature), _ptr(draft_probs), _ptr(u_accept),
+                                       _ptr(u_bonus), int(seed), int(offset),
+                                       _ptr(outputs["accept_len"]),
+                                       _ptr(outputs["accept_path"]) if n_q > 0 else None,
+                                       _ptr(outputs["bonus_id"]), _ptr(ws),
+                                       0 if ws is None else ws.numel(), _stream_ptr(stream)))
     return outputs
 
 

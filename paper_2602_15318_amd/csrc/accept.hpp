@@ -31,8 +31,10 @@ struct SampleArgs {
   const int32_t *draft_ids;  // [B*n_q]
   const int32_t *parent;     // [n_q] (parent_stride 0) or [B, parent_stride], or nullptr
   int32_t parent_stride;
-  const float *u_accept;     // [B, n_q]
-  const float *u_bonus;      // [B]
+  const float *u_accept;     // [B, n_q], or nullptr: generated from (seed, offset)
+  const float *u_bonus;      // [B], or nullptr
+  const float *draft_q;      // [M, V] draft distribution of every row's children, or nullptr
+  uint64_t seed, offset;     // key and counter prefix of the generated uniforms
   float *stats;              // [M, kStatChunks, 2]: max and sum of exponentials per chunk
   float *blk_sum;            // [M, ceil(V / 256)]: sum of exponentials per block, relative to the
                              // max of the block's chunk (chunk = ceil(blocks / 64) blocks)

@@ -557,7 +557,9 @@ size_t sparrow_accept_workspace(int32_t dtype, int32_t B, int32_t n_q, int32_t h
 // Shared body of the greedy and the stochastic acceptance.  sample == nullptr: greedy.
 struct SampleParams {
   float temperature;
-  const float *u_accept, *u_bonus;
+  const float *u_accept, *u_bonus;   // both given, or both NULL (generated from seed / offset)
+  const float *draft_q;              // NULL: deterministic-children rule
+  uint64_t seed, offset;
 };
 
 static size_t accept_sample_extra(int M, int vocab, size_t *logits_bytes, size_t *stats_bytes) {
@@ -603,8 +605,11 @@ static int accept_body(int32_t dtype, const void *hidden_rows, const void *lm_he
       return fail(SPARROW_ERR_INVALID_ARG, "temperature must be finite and > 0");
     if (vocab > kSampleMaxVocab)
       return fail(SPARROW_ERR_UNSUPPORTED, "vocab = %d exceeds %d (stochastic acceptance)", vocab, kSampleMaxVocab);
-    if (!sample->u_bonus || (n_q > 0 && !sample->u_accept))
-      return fail(SPARROW_ERR_INVALID_ARG, "NULL pointer among u_accept/u_bonus");
+    const bool generated = !sample->u_bonus && !sample->u_accept;
+    if (!generated && (!sample->u_bonus || (n_q > 0 && !sample->u_accept)))
+      return fail(SPARROW_ERR_INVALID_ARG, "u_accept and u_bonus must both be given or both be NULL");
+    if (sample->draft_q && !aligned16(sample->draft_q))
+      return fail(SPARROW_ERR_INVALID_ARG, "draft_probs must be 16-byte aligned");
   }
   if (!aligned16(hidden_rows) || !aligned16(lm_head))
     return fail(SPARROW_ERR_INVALID_ARG, "hidden_rows and lm_head must be 16-byte aligned");
@@ -640,6 +645,7 @@ static int accept_body(int32_t dtype, const void *hidden_rows, const void *lm_he
   s.logits = a.logits; s.draft_ids = draft_ids; s.parent = parent;
   s.parent_stride = a.parent_stride;
   s.u_accept = sample->u_accept; s.u_bonus = sample->u_bonus;
+  s.draft_q = sample->draft_q; s.seed = sample->seed; s.offset = sample->offset;
   s.stats = (float *)((char *)workspace + base + logits_bytes);
   s.blk_sum = (float *)((char *)workspace + base + logits_bytes + stats_bytes);
   s.accept_len = accept_len; s.accept_path = accept_path; s.bonus_id = bonus_id;
@@ -679,7 +685,24 @@ int sparrow_accept_sample_trees(int32_t dtype, const void *hidden_rows, const vo
                                 const float *u_bonus, int32_t *accept_len, int32_t *accept_path,
                                 int32_t *bonus_id, void *workspace, size_t workspace_bytes,
                                 void *hip_stream) {
-  const SampleParams sp_ = {temperature, u_accept, u_bonus};
+  const SampleParams sp_ = {temperature, u_accept, u_bonus, nullptr, 0, 0};
+  if (!u_bonus || (n_q > 0 && !u_accept)) {
+    g_err[0] = 0;
+    return fail(SPARROW_ERR_INVALID_ARG, "NULL pointer among u_accept/u_bonus");
+  }
+  return accept_body(dtype, hidden_rows, lm_head, draft_ids, parent, parent_stride, B, n_q, hidden,
+                     vocab, nullptr, accept_len, accept_path, bonus_id, workspace, workspace_bytes,
+                     hip_stream, &sp_);
+}
+
+int sparrow_accept_sample_q(int32_t dtype, const void *hidden_rows, const void *lm_head,
+                            const int32_t *draft_ids, const int32_t *parent, int32_t parent_stride,
+                            int32_t B, int32_t n_q, int32_t hidden, int32_t vocab, float temperature,
+                            const float *draft_probs, const float *u_accept, const float *u_bonus,
+                            uint64_t seed, uint64_t offset, int32_t *accept_len,
+                            int32_t *accept_path, int32_t *bonus_id, void *workspace,
+                            size_t workspace_bytes, void *hip_stream) {
+  const SampleParams sp_ = {temperature, u_accept, u_bonus, draft_probs, seed, offset};
   return accept_body(dtype, hidden_rows, lm_head, draft_ids, parent, parent_stride, B, n_q, hidden,
                      vocab, nullptr, accept_len, accept_path, bonus_id, workspace, workspace_bytes,
                      hip_stream, &sp_);
