@@ -205,3 +205,23 @@ def test_debug_validators_on_device_arrays(sp):
     with pytest.raises(sp.SparrowError) as e:
         sp.debug_validate_text_idx(tix, c.cu_seqlens, c.cu_text)
     assert e.value.code == -1 and "sequence 5" in str(e.value)
+
+
+def test_stream_read_shapes_run(sp):
+    """The measurement aid (a kernel that only reads a byte range) in every launch shape bench.py
+    sweeps: all four numbers of loads in flight, both sweep orders, ragged sizes.  It computes
+    nothing that could be compared; the calls must succeed and leave the buffer untouched."""
+    import torch
+    buf = torch.arange(3 * 1024 * 1024 + 5000, dtype=torch.int32, device="cuda")      # 12.6 MB
+    keep = buf.clone()
+    sink = torch.zeros(1, dtype=torch.int32, device="cuda")
+    for in_flight in (2, 4, 8, 16):
+        for regions in (0, 1):
+            for wgs in (1, 256, 2048):
+                sp.stream_read(buf, sink, shape=(wgs, in_flight, regions))
+    sp.stream_read(buf[:4], sink)                     # 16 bytes: the shortest range
+    sp.stream_read(buf, sink)
+    torch.cuda.synchronize()
+    assert torch.equal(buf, keep)
+    with pytest.raises(sp.SparrowError):
+        sp.stream_read(buf, sink, shape=(256, 3, 0))
