@@ -254,6 +254,116 @@ draft_qkv_mfma_kernel(DraftQkvArgs a) {
 }
 
 // ---------------------------------------------------------------------------------------------
+// One activation row (the chain draft's one new token per step), bf16: no matrix cores, no LDS.
+// A wavefront owns one output feature (FC) or one rotary pair of a head (QKV).  It issues every
+// load of its weight row(s) at once (KS loads of 1 KB, each contiguous), then fetches the
+// activation row (14 KB at most, shared by all wavefronts through L2), multiplies and reduces
+// across its lanes on the vector ALU.  With ~100 registers per lane a compute unit holds 16 such
+// wavefronts, i.e. ~200 KB of weight loads in flight, against 112 KB for the matrix-core kernel
+// whose 16 KB of LDS staging per wavefront allows one workgroup per compute unit; at one row the
+// matrix cores have nothing to offer (16 x fewer products than a tile holds).
+// ---------------------------------------------------------------------------------------------
+template <int KS>             // K / 512: 14 or 16 for Eq. 1 (K = 2H)
+__global__ void __launch_bounds__(256)
+hsr_fc_gemv_kernel(HsrFcArgs a) {
+  typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+  const int lane = threadIdx.x & 63;
+  const int nfeat = blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int H = a.H;
+  if (nfeat >= H) return;
+  const bf16_t *W = (const bf16_t *)a.w + (int64_t)nfeat * (2 * H) + 8 * lane;
+  u32x4 wv[KS];
+#pragma unroll
+  for (int s = 0; s < KS; ++s) wv[s] = __builtin_nontemporal_load((const u32x4 *)(W + kSlice * s));
+  const int tok = min(max(a.token_ids[0], 0), a.vocab - 1);
+  const bf16_t *E = (const bf16_t *)a.embed + (int64_t)tok * H + 8 * lane;
+  const bf16_t *Hp = (const bf16_t *)a.h_prev + 8 * lane;
+  u32x4 xv[KS];
+#pragma unroll
+  for (int s = 0; s < KS; ++s)     // the first KS / 2 slices meet the embedding, the rest the hidden state
+    xv[s] = *(const u32x4 *)(s < KS / 2 ? E + kSlice * s : Hp + kSlice * (s - KS / 2));
+  float acc = 0.f;
+#pragma unroll
+  for (int s = 0; s < KS; ++s) {
+    const unsigned int w4[4] = {wv[s].x, wv[s].y, wv[s].z, wv[s].w};
+    const unsigned int x4[4] = {xv[s].x, xv[s].y, xv[s].z, xv[s].w};
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+      acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, w4[e]), __builtin_bit_cast(bf16x2, x4[e]),
+                                            acc, false);
+  }
+  acc = wave_sum_valu(acc);
+  if (lane == 0) {
+    const float b = a.bias != nullptr ? bf16_to_f32(((const bf16_t *)a.bias)[nfeat]) : 0.f;
+    ((bf16_t *)a.z)[nfeat] = f32_to_bf16(acc + b);
+  }
+}
+
+template <int KS>             // H / 512: 7 or 8
+__global__ void __launch_bounds__(256)
+draft_qkv_gemv_kernel(DraftQkvArgs a) {
+  const int lane = threadIdx.x & 63;
+  const int half = a.d >> 1;
+  const int pair = blockIdx.x * 4 + (threadIdx.x >> 6);      // (head, feature of the first half)
+  const int n_heads = a.Hq + 2 * a.Hkv;
+  if (pair >= n_heads * half) return;
+  const int hd = pair / half, f = pair - hd * half;
+  const int H = a.H;
+  const bf16_t *W0 = (const bf16_t *)a.w + ((int64_t)hd * a.d + f) * H + 8 * lane;
+  const bf16_t *W1 = W0 + (int64_t)half * H;
+  u32x4 w0[KS], w1[KS];
+#pragma unroll
+  for (int s = 0; s < KS; ++s) {
+    w0[s] = __builtin_nontemporal_load((const u32x4 *)(W0 + kSlice * s));
+    w1[s] = __builtin_nontemporal_load((const u32x4 *)(W1 + kSlice * s));
+  }
+  // epilogue operands ahead of the arithmetic
+  const bool is_v = hd >= a.Hq + a.Hkv;
+  float b0 = 0.f, b1 = 0.f;
+  if (a.bias != nullptr) {
+    b0 = bf16_to_f32(((const bf16_t *)a.bias)[hd * a.d + f]);
+    b1 = bf16_to_f32(((const bf16_t *)a.bias)[hd * a.d + f + half]);
+  }
+  const float cs = a.rope_cos[f], sn = a.rope_sin[f];
+  const bf16_t *Z = (const bf16_t *)a.z + 8 * lane, *G = (const bf16_t *)a.gamma + 8 * lane;
+  float s0 = 0.f, s1 = 0.f, ssq = 0.f;
+#pragma unroll
+  for (int s = 0; s < KS; ++s) {
+    float xf[8], gf[8], a0[8], a1[8];
+    Elem<bf16_t>::unpack(*(const u32x4 *)(Z + kSlice * s), xf);
+    Elem<bf16_t>::unpack(*(const u32x4 *)(G + kSlice * s), gf);
+    Elem<bf16_t>::unpack(w0[s], a0);
+    Elem<bf16_t>::unpack(w1[s], a1);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const float u = xf[e] * gf[e];
+      ssq = fmaf(xf[e], xf[e], ssq);
+      s0 = fmaf(a0[e], u, s0);
+      s1 = fmaf(a1[e], u, s1);
+    }
+  }
+  s0 = wave_sum_valu(s0); s1 = wave_sum_valu(s1); ssq = wave_sum_valu(ssq);
+  if (lane != 0) return;
+  const float rstd = __builtin_amdgcn_rsqf(ssq / (float)H + a.eps);
+  const float y0 = fmaf(s0, rstd, b0), y1 = fmaf(s1, rstd, b1);
+  float o0 = y0, o1 = y1;
+  if (!is_v) {
+    o0 = y0 * cs - y1 * sn;
+    o1 = y1 * cs + y0 * sn;
+  }
+  bf16_t *dst;
+  if (hd < a.Hq) {
+    dst = (bf16_t *)a.q_out + (int64_t)hd * a.d;
+  } else {
+    const int c = is_v ? hd - a.Hq - a.Hkv : hd - a.Hq;
+    dst = (bf16_t *)(is_v ? a.v_cache : a.k_cache) + (int64_t)a.kv_rows[0] * a.stride_tok +
+          (int64_t)c * a.stride_head;
+  }
+  dst[f] = f32_to_bf16(o0);
+  dst[f + half] = f32_to_bf16(o1);
+}
+
+// ---------------------------------------------------------------------------------------------
 // plain-ALU versions: any dtype, any H.  One wavefront per output feature (FC) or rotary pair.
 // ---------------------------------------------------------------------------------------------
 template <typename T>
@@ -366,6 +476,12 @@ bool hsr_mfma_supported(int dtype, int H) {
 
 hipError_t launch_hsr_fc(int dtype, const HsrFcArgs &a, hipStream_t st) {
   const int rbs = (a.M + 15) / 16;
+  if (hsr_mfma_supported(dtype, a.H) && a.M == 1) {      // one row: a wavefront per output feature
+    const dim3 grid((a.H + 3) / 4);
+    if (a.H == 7 * kSlice) hipLaunchKernelGGL(hsr_fc_gemv_kernel<14>, grid, dim3(256), 0, st, a);
+    else hipLaunchKernelGGL(hsr_fc_gemv_kernel<16>, grid, dim3(256), 0, st, a);
+    return hipGetLastError();
+  }
   if (hsr_mfma_supported(dtype, a.H)) {
     const dim3 grid(a.H / 16, rbs);
     // K = 2H: two slices per wavefront
@@ -381,6 +497,12 @@ hipError_t launch_hsr_fc(int dtype, const HsrFcArgs &a, hipStream_t st) {
 hipError_t launch_draft_qkv(int dtype, const DraftQkvArgs &a, hipStream_t st) {
   const int rbs = (a.M + 15) / 16;
   const int n_heads = a.Hq + 2 * a.Hkv;
+  if (hsr_mfma_supported(dtype, a.H) && a.M == 1) {      // one row: a wavefront per rotary pair
+    const dim3 grid((n_heads * (a.d / 2) + 3) / 4);
+    if (a.H == 7 * kSlice) hipLaunchKernelGGL(draft_qkv_gemv_kernel<7>, grid, dim3(256), 0, st, a);
+    else hipLaunchKernelGGL(draft_qkv_gemv_kernel<8>, grid, dim3(256), 0, st, a);
+    return hipGetLastError();
+  }
   if (hsr_mfma_supported(dtype, a.H)) {
     // two tiles per workgroup (d / 16 tiles per head: an even number): 144 workgroups at 36 heads
     // of 128 stay within one round on 256 compute units

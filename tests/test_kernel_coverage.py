@@ -65,6 +65,10 @@ COVERAGE = {
     "hsr_fc_generic_kernel<unsigned short>": (H, "test_hsr_fc", "bf16-4-2-64-512"),
     "hsr_fc_mfma_kernel<7, 2>": (H, "test_hsr_fc", "bf16-28-4-128-3584"),
     "hsr_fc_mfma_kernel<8, 2>": (H, "test_hsr_fc", "bf16-32-8-128-4096"),
+    "hsr_fc_gemv_kernel<14>": (H, "test_hsr_fc", "bf16-28-4-128-3584, one row"),
+    "hsr_fc_gemv_kernel<16>": (H, "test_hsr_fc", "bf16-32-8-128-4096, one row"),
+    "draft_qkv_gemv_kernel<7>": (H, "test_draft_qkv_append", "bf16-28-4-128-3584, one row"),
+    "draft_qkv_gemv_kernel<8>": (H, "test_draft_qkv_append", "bf16-32-8-128-4096, one row"),
     "draft_qkv_generic_kernel<float>": (H, "test_draft_qkv_append", "f32-4-1-64-256"),
     "draft_qkv_generic_kernel<unsigned short>": (H, "test_draft_qkv_append", "bf16-4-2-64-512"),
     "draft_qkv_mfma_kernel<7, 1>": (H, "test_draft_qkv_append", "bf16-28-4-128-3584"),
