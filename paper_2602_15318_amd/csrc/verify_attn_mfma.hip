@@ -70,8 +70,8 @@ __device__ __forceinline__ float quad_sum(float v) {
 // all 256 registers with one step in flight.
 // kPrefetch = steps in flight in registers.  The whole split of a workgroup is only a handful of
 // steps at decode-time sizes (7 at 26k context on 256 compute units), so a deep look-ahead turns
-// the kernel into "load most of it, then compute": depth 1 is fastest there, depth 2 once the
-// splits get long (batches, very long contexts).
+// the kernel into "load most of it, then compute": depth 3-4 is slower there, depth 2 wins from
+// about four steps on, depth 1 for the shortest splits.
 // Per-sequence split length in tokens (split_len of the sequence), worked out by the host so that
 // the kernel's way to its first load holds no integer division.
 struct PieceTable {
@@ -109,7 +109,7 @@ verify_partial_mfma_kernel(VerifyArgs a, SeqTable tab, PieceTable pt, int rbs, i
   //  - flat (x only; for ragged batches, where the first shape would launch mostly padding):
   //    x enumerates (global split, KV head) and the sequence is searched in the split table.
   const int xj = blockIdx.x >> 3, xcd = blockIdx.x & 7;
-  const int bz = flat ? 0 : blockIdx.z;
+  const int bz = blockIdx.z;               // (0 on the flat grid: no need to wait for `flat` to know it)
   const int cl0_z = tab.cu_len[bz], cl1_z = tab.cu_len[bz + 1];
   const int cs0_z = tab.cu_split[bz], cs1_z = tab.cu_split[bz + 1];
   const int piece_z = pt.piece[bz];
@@ -588,7 +588,7 @@ hipError_t launch_verify_partial_mfma(const VerifyArgs &a, const SeqTable &tab, 
     hipLaunchKernelGGL((verify_partial_mfma_kernel<1, 2>), grid, block, kLdsBytes, st, a, tab, pt, rbs, flat);
   else if (qt == 2)
     hipLaunchKernelGGL((verify_partial_mfma_kernel<2, 2>), grid, block, kLdsBytes, st, a, tab, pt, rbs, flat);
-  else if (steps <= 10)
+  else if (steps <= 3)       // (a second step in flight pays from 4 steps on: -0.15 us at the 7 steps of a 26k chain)
     hipLaunchKernelGGL((verify_partial_mfma_kernel<1, 1>), grid, block, kLdsBytes, st, a, tab, pt, rbs, flat);
   else
     hipLaunchKernelGGL((verify_partial_mfma_kernel<2, 1>), grid, block, kLdsBytes, st, a, tab, pt, rbs, flat);
