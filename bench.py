@@ -52,6 +52,10 @@ def main() -> int:
                          "C4) and on the dynamic-tree shapes (`other_configs`, `roofline_c3`)")
     ap.add_argument("--profile-only", action="store_true",
                     help="run warmup + steps only (for rocprofv3), skip the per-op timing legs")
+    ap.add_argument("--profile-config", choices=["C3", "tree30", "tree48"], default=None,
+                    help="for rocprofv3: run nothing but verify attention on this workload (8 distinct "
+                         "layers at the 26,112-token context, --steps passes) and the counter "
+                         "calibration kernel; no C5 step")
     args = ap.parse_args()
     if args.gpus != 1:
         print(f"bench.py: this build runs on one GPU only (no collectives, no sharding); "
@@ -72,6 +76,37 @@ def main() -> int:
     def dev(x, dt=None):
         t = torch.from_numpy(np.ascontiguousarray(x)).to("cuda")
         return t if dt is None else t.to(dt)
+
+    if args.profile_config is not None:
+        # one workload's verify attention alone, so that every dispatch of its kernel instance in
+        # the counter output belongs to it (the tree instances share launch shapes)
+        if args.profile_config == "C3":
+            par_p = wl.parent_of(wl.C3, args.seed)
+        elif args.profile_config == "tree30":
+            par_p = wl.pruned_tree(args.seed, 30, (4, 3, 2, 2))
+        else:
+            par_p = wl.pruned_tree(args.seed, 48, (5, 3, 2, 2, 1))
+        cs = [wl.verify_case(wl.C3, args.seed, layer=l, n_q=len(par_p), parent=par_p) for l in range(8)]
+        ls = [(dev(c.q, bf16), dev(c.k, bf16), dev(c.v, bf16)) for c in cs]
+        par_d = dev(par_p)
+        tot = int(cs[0].cu_seqlens[-1])
+        ws_p = torch.empty(sp.verify_attn_workspace_bytes(*ls[0], 1, len(par_p), tot), dtype=torch.uint8,
+                           device="cuda")
+        outs = [torch.empty_like(q) for q, _, _ in ls]
+        for _ in range(args.warmup + args.steps):
+            for (q, k, v), o in zip(ls, outs):
+                sp.verify_attn(q, k, v, cs[0].cu_seqlens, par_d, len(par_p), out=o, want_lse=False, workspace=ws_p)
+        torch.cuda.synchronize()
+        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").fill_(1.0)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            torch.add(src, 1.0, out=dst)
+        torch.cuda.synchronize()
+        print(json.dumps({"profile_config": args.profile_config, "n_q": len(par_p), "tokens": tot,
+                          "layers": 8, "passes": args.warmup + args.steps,
+                          "calibration": "torch.add(src, 1.0, out=dst), 2^28 floats: 1 GiB read, "
+                                         "1 GiB written per launch"}))
+        return 0
 
     # ---------------------------------------------------------------- inputs (seeded, synthetic)
     t_gen = time.time()
