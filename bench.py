@@ -77,6 +77,13 @@ def main() -> int:
         t = torch.from_numpy(np.ascontiguousarray(x)).to("cuda")
         return t if dt is None else t.to(dt)
 
+    def head_major_pair(k, v):
+        # [T, Hkv, d] views of one [Hkv, T, 2, d] allocation: every KV head's tokens are contiguous
+        # and a token's K row is followed by its V row, so a workgroup (one KV head, one split)
+        # streams ONE contiguous 200 KB range
+        kv = torch.stack([dev(k, bf16).permute(1, 0, 2), dev(v, bf16).permute(1, 0, 2)], dim=2).contiguous()
+        return kv[:, :, 0, :].permute(1, 0, 2), kv[:, :, 1, :].permute(1, 0, 2), kv
+
     if args.profile_config is not None:
         # one workload's verify attention alone, so that every dispatch of its kernel instance in
         # the counter output belongs to it (the tree instances share launch shapes)
@@ -87,7 +94,7 @@ def main() -> int:
         else:
             par_p = wl.pruned_tree(args.seed, 48, (5, 3, 2, 2, 1))
         cs = [wl.verify_case(wl.C3, args.seed, layer=l, n_q=len(par_p), parent=par_p) for l in range(8)]
-        ls = [(dev(c.q, bf16), dev(c.k, bf16), dev(c.v, bf16)) for c in cs]
+        ls = [(dev(c.q, bf16),) + head_major_pair(c.k, c.v)[:2] for c in cs]
         par_d = dev(par_p)
         tot = int(cs[0].cu_seqlens[-1])
         ws_p = torch.empty(sp.verify_attn_workspace_bytes(*ls[0], 1, len(par_p), tot), dtype=torch.uint8,
@@ -113,12 +120,6 @@ def main() -> int:
     with ThreadPoolExecutor(max_workers=8) as pool:
         cases = list(pool.map(lambda l: wl.verify_case(cfg, args.seed, layer=l), range(cfg.n_layers)))
     cu = cases[0].cu_seqlens
-    def head_major_pair(k, v):
-        # [T, Hkv, d] views of one [Hkv, T, 2, d] allocation: every KV head's tokens are contiguous
-        # and a token's K row is followed by its V row, so a workgroup (one KV head, one split)
-        # streams ONE contiguous 200 KB range
-        kv = torch.stack([dev(k, bf16).permute(1, 0, 2), dev(v, bf16).permute(1, 0, 2)], dim=2).contiguous()
-        return kv[:, :, 0, :].permute(1, 0, 2), kv[:, :, 1, :].permute(1, 0, 2), kv
     layers, kv_store = [], []
     for c in cases:
         k_, v_, kv_ = head_major_pair(c.k, c.v)
@@ -458,12 +459,13 @@ def main() -> int:
     # ---------------------------------------------------------------- other shapes, on request
     if not args.no_other_configs:
         def time_verify(cfg_o, n_layers_o, n_q_o=None, parent_o=None):
-            """Verify attention per layer on `cfg_o`: distinct K/V per layer (token-major) so that
-            the Infinity Cache cannot serve the stream; graph replay, HIP events."""
+            """Verify attention per layer on `cfg_o`: distinct K/V per layer so that the Infinity
+            Cache cannot serve the stream; graph replay, HIP events."""
             kw = {} if n_q_o is None else {"n_q": n_q_o, "parent": parent_o}
             cs = [wl.verify_case(cfg_o, args.seed, layer=l, **kw) for l in range(n_layers_o)]
             c0 = cs[0]
-            ls = [(dev(c.q, bf16), dev(c.k, bf16), dev(c.v, bf16)) for c in cs]
+            # the same K/V layout as the C5 step: head-major, a token's K and V rows interleaved
+            ls = [(dev(c.q, bf16),) + head_major_pair(c.k, c.v)[:2] for c in cs]
             par = None if c0.parent is None else dev(c0.parent)
             nb = len(c0.cu_seqlens) - 1
             tot = int(c0.cu_seqlens[-1])

@@ -122,7 +122,12 @@ def test_draft_input_chain_feeds_window_attention(sp, oracle):
     o_ref, _ = oracle.draft_window_attn(host(q), host(kc), host(vc), dc.cu_seqlens, dc.text_idx,
                                         dc.cu_text, dc.window)
     _close(host(out), o_ref, dt, "chain attention on the device's q/k/v")
-    # the oracle's own chain, end to end (bf16 rounding of z, q, k, v in between on the device)
+    # the oracle's own chain, end to end.  The device rounds z, q, k and v to bf16 between the
+    # stages (2^-9 relative each), the oracle's chain does not: a score q.k/sqrt(d) of magnitude up
+    # to ~6 then moves by up to ~6 * 3 * 2^-9 = 0.035, its softmax weight by 3.5 % of itself, and an
+    # output element (a weighted mean of v's of magnitude up to ~1.5) by up to ~0.05, on top of the
+    # 2e-2 of the attention itself when every rounding goes one way: 6e-2 bounds the worst case,
+    # the stage-by-stage checks above are the tight ones
     k2, v2 = dc.k.astype(np.float64), dc.v.astype(np.float64)
     q2, kk, vv = oracle.draft_qkv(z_ref, c.norm_weight, c.eps, c.w_qkv, c.b_qkv, c.rope_cos,
                                   c.rope_sin, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim)
