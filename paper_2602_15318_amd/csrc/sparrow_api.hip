@@ -356,7 +356,7 @@ int sparrow_debug_validate_text_idx(const int32_t *text_idx, const int32_t *cu_s
 }
 
 const char *sparrow_last_error(void) { return g_err; }
-const char *sparrow_version(void) { return "0.1"; }
+const char *sparrow_version(void) { return "0.2"; }
 
 // ------------------------------------------------------------------ draft window attention
 size_t sparrow_draft_window_attn_workspace(const sparrow_attn_desc *, int32_t, int32_t) { return 0; }

@@ -82,3 +82,31 @@ def test_static_scratch_entry_rejects_what_does_not_fit(sp):
     with pytest.raises(sp.SparrowError) as e:
         sp.verify_attn_static(q, k, k, np.array([0, 3], dtype=np.int32), None, n_q, out)
     assert e.value.code == -1
+
+
+def test_static_scratch_entry_in_a_captured_graph(sp):
+    """The use the entry point is for: captured in a HIP graph (after one call outside capture,
+    which looks the scratch address up), replayed several times with eager work in between, each
+    replay equal to the eager result bit for bit."""
+    cfg = _cfg()
+    c = wl.verify_case(cfg, seed=5, layouts=(((wl.TEXT, 30), (wl.VISUAL, 5000), (wl.TEXT, 70)),), n_q=8,
+                       parent=None)
+    q, k, v = dev(c.q, "bf16"), dev(c.k, "bf16"), dev(c.v, "bf16")
+    eager = torch.zeros_like(q)
+    sp.verify_attn_static(q, k, v, c.cu_seqlens, None, 8, eager)
+    torch.cuda.synchronize()
+    out = torch.zeros_like(q)
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        sp.verify_attn_static(q, k, v, c.cu_seqlens, None, 8, out)
+    other = wl.verify_case(cfg, seed=6, layouts=(((wl.TEXT, 900),),), n_q=3, parent=None)
+    oq, ok_, ov = dev(other.q, "bf16"), dev(other.k, "bf16"), dev(other.v, "bf16")
+    scratch_user = torch.zeros_like(oq)
+    for rep in range(3):
+        out.zero_()
+        # an eager call on the same scratch between the replays leaves other contents in it
+        sp.verify_attn_static(oq, ok_, ov, other.cu_seqlens, None, 3, scratch_user)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, eager), f"replay {rep}"
