@@ -244,6 +244,13 @@ def main() -> int:
     def accept_sample():
         sp.accept_sample(hidden, lm_head, draft_ids, None, 1, n_q, 1.0, s_ua, s_ub, workspace=ws_s,
                          outputs=s_out)
+    # ... and against a sampled draft: a flat draft distribution per row and random drafts, so the
+    # first node is rejected (one pass over the row's logits and draft probabilities for the
+    # residual) and the bonus token is drawn from the residual; uniforms generated in the kernel
+    s_q = torch.full((n_q + 1, cfg.vocab), 1.0 / cfg.vocab, dtype=torch.float32, device="cuda")
+    def accept_sample_q():
+        sp.accept_sample_q(hidden, lm_head, draft_ids, None, 1, n_q, 1.0, draft_probs=s_q, seed=1, offset=0,
+                           workspace=ws_s, outputs=s_out)
     # dynamic draft tree, configuration 30-4-8 (not part of `value`): top-8 log-probabilities of 8
     # frontier rows over the full vocabulary, one level expansion, final selection
     t_hid = hidden[:8].contiguous()
@@ -267,6 +274,7 @@ def main() -> int:
             topk_call(); tree_tail()
         for _ in range(5):
             accept_sample()
+            accept_sample_q()
         torch.cuda.synchronize()
         # calibration for the HBM-traffic counters: a plain copy kernel of known size
         # (1 GiB read + 1 GiB written per launch) in the same profile
@@ -298,6 +306,7 @@ def main() -> int:
     us_draft = time_graph(capture(draft_many), REPS) / 28
     us_accept = time_graph(capture(accept), REPS)
     us_accept_sample = time_graph(capture(accept_sample), REPS)
+    us_accept_sample_q = time_graph(capture(accept_sample_q), REPS)
     us_topk = time_graph(capture(topk_call), REPS)
     us_tree_tail = time_graph(capture(tree_tail), REPS)
 
@@ -431,6 +440,7 @@ def main() -> int:
             "max_abs_diff_to_per_layer_calls": round(batch_diff, 6),
             "plain_read_of_the_same_1p5_gb_gbps": sustained},
         "accept_sample_t1_us": round(us_accept_sample, 2),
+        "accept_sample_q_t1_us": round(us_accept_sample_q, 2),
         "draft_tree_30_4_8": {"draft_topk_8rows_us": round(us_topk, 2),
                               "expand_plus_select_us": round(us_tree_tail, 2)},
         "roofline": {"bound": "hbm", "kernel": "verify_partial_mfma_kernel (split-context partial "

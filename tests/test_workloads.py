@@ -73,3 +73,16 @@ def test_cases_are_seeded_and_storage_exact():
         assert ti[-1] == d.cu_seqlens[b_ + 1] - d.cu_seqlens[b_] - 1
     w1 = wl.lm_head_weights(wl.C1)
     assert w1.shape == (1024, 256) and abs(float(w1.std()) - 0.02) < 1e-3
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py is a one-GPU program: --gpus N with N > 1 exits with a message (no GPU needed to
+    find that out)."""
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    res = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"],
+                         capture_output=True, text=True, timeout=120)
+    assert res.returncode == 2
+    assert "one GPU" in res.stderr and res.stdout.strip() == ""
