@@ -306,11 +306,16 @@ verify_partial_mfma_kernel(VerifyArgs a, SeqTable tab, PieceTable pt, int rbs, i
 #pragma unroll
         for (int i = 0; i < 4; ++i) sc[4 * j + i] = s[qt][j][i];
       if (edge) {
+        // (an opaque copy of the step's first token: without it the compiler works the token
+        // numbers, their distances to L and the shift counts out on EVERY step, ahead of the
+        // branch -- some 20 vector instructions per row tile that all but one step throw away)
+        int tb_e = tb;
+        asm volatile("" : "+s"(tb_e));
 #pragma unroll
         for (int j = 0; j < kLd; ++j)
 #pragma unroll
           for (int i = 0; i < 4; ++i) {
-            const int tok = tb + 16 * j + 4 * c4 + i;
+            const int tok = tb_e + 16 * j + 4 * c4 + i;
             const int dj = tok - L;
             const bool vis = (dj < 0) | (((anc[qt] >> (dj & 63)) & 1ull) != 0ull);
             sc[4 * j + i] = ((tok < t1) & vis) ? sc[4 * j + i] : -INFINITY;
