@@ -278,6 +278,10 @@ verify_partial_mfma_kernel(VerifyArgs a, SeqTable tab, PieceTable pt, int rbs, i
     const unsigned char *Vs = lds_at(strm, buf, 1);
     const int tb = t0 + (st * kStreams + strm) * kSub * kTile;
     f32x4 s[NA][kLd];
+    // Tree instances raise the wavefront's priority for their MFMA phases: the other wavefront of
+    // the SIMD is then in its softmax, and the matrix pipe stays fed (-3 % on the 60-node tree).
+    constexpr bool kPrio = kQT > 1;
+    if (kPrio) __builtin_amdgcn_s_setprio(1);
 #pragma unroll
     for (int j = 0; j < kLd; ++j) {
       bf16x8 ka[4];
@@ -295,6 +299,7 @@ verify_partial_mfma_kernel(VerifyArgs a, SeqTable tab, PieceTable pt, int rbs, i
     // mask, online softmax (per lane = per query row).  Scores stay unscaled until the exponent:
     // exp2(s * scale_log2 - m) is one fused multiply-add per score (scale_log2 > 0, so the
     // maximum can be taken before scaling).
+    if (kPrio) __builtin_amdgcn_s_setprio(0);
     const bool edge = tb + kSub * kTile > min(t1, L);   // uniform: split end or draft rows in reach
     if (kQT > 1) __builtin_amdgcn_sched_barrier(0);     // keep the V^T reads below the softmax
     bf16x8 pb[NA][kSub];
@@ -355,6 +360,7 @@ verify_partial_mfma_kernel(VerifyArgs a, SeqTable tab, PieceTable pt, int rbs, i
       }
     }
     if (kQT > 1) __builtin_amdgcn_sched_barrier(0);
+    if (kPrio) __builtin_amdgcn_s_setprio(1);
 #pragma unroll
     for (int mt = 0; mt < 8; ++mt) {
       const int ch = ((2 * mt + v_chb) ^ v_swz) << 4;
@@ -369,6 +375,7 @@ verify_partial_mfma_kernel(VerifyArgs a, SeqTable tab, PieceTable pt, int rbs, i
           o_acc[qt][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vt, pb[qt][u], o_acc[qt][mt], 0, 0, 0);
       }
     }
+    if (kPrio) __builtin_amdgcn_s_setprio(0);
   };
 
   // A wavefront with a partly filled set of row tiles computes all of them (the empty ones on a zero
