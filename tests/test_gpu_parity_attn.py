@@ -88,6 +88,25 @@ def test_c5_bf16_26k_chain8_layer(sp, oracle, layer):
         _draft_and_check(sp, oracle, wl.draft_case(wl.C5, 0), "C5 draft")
 
 
+@pytest.mark.parametrize("which", ["C5", "C3", "C4"])
+def test_full_size_in_the_benchmarked_kv_layout(sp, oracle, which):
+    """bench.py keeps a layer's K and V in one [Hkv, T, 2, d] allocation (head-major, a token's K
+    row followed by its V row) and hands the library [T, Hkv, d] views of it: the full-size
+    workloads once more in exactly that layout and launch configuration."""
+    import torch
+    cfg = {"C5": wl.C5, "C3": wl.C3, "C4": wl.C4}[which]
+    c = wl.verify_case(cfg, 0, layer=3)
+    kv = torch.stack([dev(c.k, "bf16").permute(1, 0, 2), dev(c.v, "bf16").permute(1, 0, 2)], dim=2).contiguous()
+    k, v = kv[:, :, 0, :].permute(1, 0, 2), kv[:, :, 1, :].permute(1, 0, 2)
+    assert k.stride(0) == 2 * cfg.head_dim and k.stride(1) > k.stride(0)
+    par = None if c.parent is None else dev(c.parent)
+    out, lse = sp.verify_attn(dev(c.q, "bf16"), k, v, c.cu_seqlens, par, c.n_q)
+    torch.cuda.synchronize()
+    ref, ref_lse = oracle.verify_attn(c.q, c.k, c.v, c.cu_seqlens, c.parent, c.n_q)
+    check_attn(host(out), ref, "bf16", f"{which} in the benchmarked layout")
+    assert np.abs(host(lse) - ref_lse).max() <= LSE_TOL["bf16"]
+
+
 # ------------------------------------------------------------------ shapes, tails, degenerate cases
 def _cfg(dtype, Hq, Hkv, d, n_q=4, window=16):
     return wl.Config("T", dtype, Hq, Hkv, d, 1, None, window, n_q, False, 64, 128)
