@@ -161,6 +161,31 @@ def test_accept_one_tree_per_sequence_and_many_rows(sp, oracle, dtype, H, V, B, 
         _check(run_accept(sp, c, B, draft_ids=ids.reshape(-1), lm_head_dev=W), r, f"planted {want}")
 
 
+@pytest.mark.parametrize("dtype,H", [("f32", 256), ("bf16", 1024), ("bf16", 3584)])
+def test_random_trees_over_a_tiny_vocabulary(sp, oracle, dtype, H):
+    """Arbitrary tree shapes (every parent drawn uniformly among the earlier nodes and the root,
+    one tree per sequence) over a vocabulary of 6 tokens: drafted tokens coincide with target
+    tokens all the time, siblings often carry the same token (the lowest node index must win), and
+    walks of every depth occur."""
+    V, B, n_q = 6, 6, 20
+    cfg = wl.Config("A", dtype, 4, 1, 64, B, None, 8, n_q, True, H, V)
+    depths = set()
+    for seed in range(6):
+        rng = np.random.default_rng(700 + seed)
+        trees = np.stack([np.array([int(rng.integers(-1, i)) for i in range(n_q)], dtype=np.int32)
+                          for _ in range(B)])
+        c = wl.accept_case(cfg, seed=seed, batch=B, n_q=n_q, parent=trees, planted=True)
+        draft = rng.integers(0, V, size=B * n_q).astype(np.int32)
+        ref = oracle.accept_step(c.hidden, c.lm_head, draft, trees, B, n_q)
+        _check(run_accept(sp, c, B, draft_ids=draft), ref, f"seed {seed}")
+        depths.update(ref["accept_len"].tolist())
+        # the same drafts on one shared tree
+        ref1 = oracle.accept_step(c.hidden, c.lm_head, draft, trees[0], B, n_q)
+        c.parent = trees[0]
+        _check(run_accept(sp, c, B, draft_ids=draft), ref1, f"seed {seed}, shared tree")
+    assert len(depths) >= 3, depths
+
+
 def test_exact_ties_take_lowest_id(sp, oracle):
     """Duplicated lm_head rows give bit-equal logits on both sides: the lower id must win, also
     when the duplicates fall into different tiles / wavefronts of the GEMM pass."""
