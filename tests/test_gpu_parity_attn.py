@@ -184,6 +184,24 @@ def test_verify_random_batches(sp, oracle, seed):
 
 
 @pytest.mark.parametrize("dtype,Hq,Hkv,d", [("f32", 4, 1, 64), ("bf16", 28, 4, 128)])
+@pytest.mark.parametrize("n_q", [5, 33, 64])
+def test_verify_arbitrary_random_trees(sp, oracle, dtype, Hq, Hkv, d, n_q):
+    """Trees of any shape (every parent drawn uniformly among the root and the earlier nodes: long
+    chains, wide stars and everything between, up to the 64 nodes the boundary takes), one per
+    sequence, against short and empty contexts, where the draft rows' mask decides most of the
+    result."""
+    cfg = _cfg(dtype, Hq, Hkv, d)
+    for seed in range(3):
+        rng = np.random.default_rng(1000 * n_q + seed)
+        lengths = (int(rng.integers(0, 400)), int(rng.integers(0, 60)), 0)
+        trees = np.stack([np.array([int(rng.integers(-1, i)) for i in range(n_q)], dtype=np.int32)
+                          for _ in lengths])
+        lay = tuple(((wl.TEXT, n),) for n in lengths)
+        c = wl.verify_case(cfg, seed=seed, layouts=lay, n_q=n_q, parent=trees, peaked=(seed == 1))
+        _verify_and_check(sp, oracle, c, f"random trees {dtype} n_q={n_q} seed {seed} {lengths}")
+
+
+@pytest.mark.parametrize("dtype,Hq,Hkv,d", [("f32", 4, 1, 64), ("bf16", 28, 4, 128)])
 def test_verify_trees(sp, oracle, dtype, Hq, Hkv, d):
     cfg = _cfg(dtype, Hq, Hkv, d)
     lay = (((wl.TEXT, 700),), ((wl.TEXT, 90),))
