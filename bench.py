@@ -191,6 +191,18 @@ def main() -> int:
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) * 1e3 / reps      # us per replay
 
+    def replay_spread(g, reps):
+        """Median and minimum of single replays (one HIP-event pair per replay): the spread behind
+        the mean that time_graph reports."""
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+        for a_, b_ in evs:
+            a_.record()
+            g.replay()
+            b_.record()
+        torch.cuda.synchronize()
+        t = sorted(a_.elapsed_time(b_) * 1e3 for a_, b_ in evs)
+        return t[len(t) // 2], t[0]
+
     # ---------------------------------------------------------------- the timed region
     g_step = capture(step)
     for _ in range(args.warmup):
@@ -299,7 +311,9 @@ def main() -> int:
     def verify_all():
         for l in range(cfg.n_layers):
             verify_layer(l)
-    us_verify_step = time_graph(capture(verify_all), REPS)
+    g_verify = capture(verify_all)
+    us_verify_step = time_graph(g_verify, REPS)
+    us_verify_median, us_verify_min = replay_spread(g_verify, REPS)
     def draft_many():                      # 28 calls back to back: per-call time without the
         for _ in range(28):                # replay launch latency of a one-kernel graph
             draft()
@@ -323,7 +337,9 @@ def main() -> int:
     def partial_all():
         for l in range(cfg.n_layers):
             verify_layer(l, passes=1)
-    us_partial = time_graph(capture(partial_all), REPS) / cfg.n_layers
+    g_partial = capture(partial_all)
+    us_partial = time_graph(g_partial, REPS) / cfg.n_layers
+    us_partial_median, us_partial_min = (x / cfg.n_layers for x in replay_spread(g_partial, REPS))
     # the measured ceiling beside the published peak: the fastest kernel found that only READS the
     # same K and V bytes (one launch per layer over the layer's K/V allocation, 28 distinct layers
     # back to back in a graph like the attention kernel), over launch shapes: workgroups of 256
@@ -420,6 +436,8 @@ def main() -> int:
         "us_per_step": round(us_step, 2),
         "verify_attn_us_per_step": round(us_verify_step, 2),
         "verify_attn_us_per_layer": round(us_layer, 3),
+        "verify_attn_us_per_layer_median_min": [round(us_verify_median / cfg.n_layers, 3),
+                                                round(us_verify_min / cfg.n_layers, 3)],
         "verify_attn_gbps": round(gbps_layer, 1),
         "verify_attn_pct_hbm_peak": round(100 * gbps_layer / HBM_PEAK_GBPS, 2),
         "verify_partial_pass_us": round(us_partial, 3),
@@ -450,6 +468,7 @@ def main() -> int:
                      "traffic_note": traffic_note,
                      "algorithmic_bytes_per_launch": bytes_verify_layer,
                      "avg_launch_us": round(us_partial, 3),
+                     "launch_us_median_min": [round(us_partial_median, 3), round(us_partial_min, 3)],
                      "op": "sparrow_verify_attn, one layer: partial pass + combine, two dependent launches",
                      "op_us": round(us_layer, 3), "op_achieved": round(gbps_layer, 1),
                      "op_frac": round(gbps_layer / HBM_PEAK_GBPS, 4),
